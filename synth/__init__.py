@@ -1,0 +1,226 @@
+"""Seeded synthetic inputs shared by the CPU oracle and the HIP path.
+
+This module holds NONE of the decoder's arithmetic: it only draws random
+numbers, casts them to the 16-bit storage formats the workloads use, and names
+the model shapes.  Both the oracle (under ``oracle/``) and the GPU library
+receive exactly the arrays produced here, so parity tests compare the two on
+identical inputs.
+
+Recipe (stand-in for the trained Qwen2.5 checkpoints the paper measures on,
+which are not available offline):
+  * matrices, embeddings, biases  ~ N(0, 0.02), rounded to the weight dtype
+  * RMSNorm gains                 ~ 1 + N(0, 0.02), rounded to the weight dtype
+  * prompt token ids              ~ U[0, vocab)
+  * visual-token embedding rows   ~ N(0, 1), rounded to the weight dtype
+  * injected KV rows (long-context decode tests) ~ N(0, 1) rounded to kv dtype
+Every tensor is produced block-wise by a counter-based Philox stream keyed by
+(seed, crc32(tensor name), block index), so the values do not depend on the
+number of threads used to generate them.
+"""
+from __future__ import annotations
+
+import os
+import zlib
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+F16 = 1
+BF16 = 2
+
+SEED_WEIGHTS = 27476
+SEED_PROMPT = 27477
+SEED_VISUAL = 27478
+SEED_KV = 27479
+
+_BLOCK = 1 << 22  # elements per independently keyed block
+
+
+@dataclass(frozen=True)
+class DecoderShape:
+    name: str
+    n_layers: int
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    intermediate: int
+    vocab: int
+    weight_dtype: int
+    kv_dtype: int
+    tie_embeddings: bool
+    qkv_bias: bool
+    rms_eps: float = 1e-6
+    rope_theta: float = 1e6
+    max_seq_len: int = 1024
+
+    @property
+    def q_dim(self) -> int:
+        return self.n_q_heads * self.head_dim
+
+    @property
+    def kv_dim(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+    @property
+    def qkv_rows(self) -> int:
+        return self.q_dim + 2 * self.kv_dim
+
+    def with_(self, **kw) -> "DecoderShape":
+        return replace(self, **kw)
+
+    def weight_bytes_per_token(self) -> int:
+        """Bytes of parameters one decode step must read (16-bit storage)."""
+        H, I, V = self.hidden, self.intermediate, self.vocab
+        per_layer = (self.qkv_rows * H + H * self.q_dim + 2 * I * H + H * I) * 2
+        per_layer += 2 * H * 2 + (self.qkv_rows * 2 if self.qkv_bias else 0)
+        return self.n_layers * per_layer + V * H * 2 + H * 2 + H * 2
+
+    def kv_bytes_per_context_token(self) -> int:
+        return self.n_layers * 2 * self.kv_dim * 2
+
+
+TINY = DecoderShape("tiny", 2, 256, 4, 2, 64, 704, 2048, F16, F16,
+                    tie_embeddings=False, qkv_bias=False, max_seq_len=64)
+QWEN_0P5B = DecoderShape("qwen2.5-0.5b-shaped", 24, 896, 14, 2, 64, 4864, 151936,
+                         BF16, BF16, tie_embeddings=True, qkv_bias=True,
+                         max_seq_len=128 + 256)
+QWEN_1P5B = DecoderShape("qwen2.5-1.5b-shaped", 28, 1536, 12, 2, 128, 8960, 151936,
+                         BF16, BF16, tie_embeddings=True, qkv_bias=True,
+                         max_seq_len=512 + 128)
+QWEN_7B = DecoderShape("qwen2.5-7b-shaped", 28, 3584, 28, 4, 128, 18944, 152064,
+                       BF16, BF16, tie_embeddings=False, qkv_bias=True,
+                       max_seq_len=8192 + 64)
+
+SHAPES = {s.name: s for s in (TINY, QWEN_0P5B, QWEN_1P5B, QWEN_7B)}
+
+
+# ---------------------------------------------------------------------------
+# storage-format casts (round to nearest even); these define the inputs, they
+# are not part of the decoder
+# ---------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def to_bits(x: np.ndarray, dtype: int) -> np.ndarray:
+    return f32_to_bf16_bits(x) if dtype == BF16 else f32_to_f16_bits(x)
+
+
+def from_bits(b: np.ndarray, dtype: int) -> np.ndarray:
+    return bf16_bits_to_f32(b) if dtype == BF16 else f16_bits_to_f32(b)
+
+
+# ---------------------------------------------------------------------------
+# counter-based normal draws
+# ---------------------------------------------------------------------------
+def _block_normal(seed: int, name_key: int, block: int, n: int) -> np.ndarray:
+    gen = np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64((name_key << 32) | block)]))
+    return gen.standard_normal(n, dtype=np.float32)
+
+
+def _n_threads() -> int:
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:  # pragma: no cover
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def normal_bits(seed: int, name: str, shape, dtype: int, mean: float = 0.0, std: float = 0.02,
+                pool: ThreadPoolExecutor | None = None) -> np.ndarray:
+    """Tensor ~ N(mean, std) rounded to `dtype`, returned as uint16 storage bits."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.uint16)
+    key = zlib.crc32(name.encode())
+
+    def work(b: int) -> None:
+        lo = b * _BLOCK
+        hi = min(n, lo + _BLOCK)
+        z = _block_normal(seed, key, b, hi - lo)
+        z *= np.float32(std)
+        if mean != 0.0:
+            z += np.float32(mean)
+        out[lo:hi] = to_bits(z, dtype)
+
+    blocks = range((n + _BLOCK - 1) // _BLOCK)
+    if pool is None or len(blocks) == 1:
+        for b in blocks:
+            work(b)
+    else:
+        list(pool.map(work, blocks))
+    return out.reshape(shape)
+
+
+def make_weights(shape: DecoderShape, seed: int = SEED_WEIGHTS, n_layers: int | None = None) -> dict:
+    """Random decoder parameters as uint16 storage bits (row-major [out, in]).
+
+    Layout of the returned dict:
+      embed [V,H], lm_head [V,H] or None when tied, final_norm [H],
+      layers: list of dicts with attn_norm [H], wqkv [(n_q+2 n_kv) d, H] with rows
+      ordered Q heads | K heads | V heads, bqkv [(n_q+2 n_kv) d] or None,
+      wo [H, n_q d], mlp_norm [H], w_gate_up [2 I, H] with rows gate | up,
+      w_down [H, I].
+    `n_layers` truncates the depth (layer tensors keep their per-layer names, so
+    a truncated model is a prefix of the full one).
+    """
+    L = shape.n_layers if n_layers is None else n_layers
+    H, I, V, wd = shape.hidden, shape.intermediate, shape.vocab, shape.weight_dtype
+    with ThreadPoolExecutor(_n_threads()) as pool:
+        def mat(name, shp):
+            return normal_bits(seed, name, shp, wd, 0.0, 0.02, pool)
+
+        def gain(name):
+            return normal_bits(seed, name, (H,), wd, 1.0, 0.02, None)
+
+        w = {
+            "embed": mat("embed", (V, H)),
+            "lm_head": None if shape.tie_embeddings else mat("lm_head", (V, H)),
+            "final_norm": gain("final_norm"),
+            "layers": [],
+        }
+        for l in range(L):
+            p = f"layer{l}."
+            w["layers"].append({
+                "attn_norm": gain(p + "attn_norm"),
+                "wqkv": mat(p + "wqkv", (shape.qkv_rows, H)),
+                "bqkv": mat(p + "bqkv", (shape.qkv_rows,)) if shape.qkv_bias else None,
+                "wo": mat(p + "wo", (H, shape.q_dim)),
+                "mlp_norm": gain(p + "mlp_norm"),
+                "w_gate_up": mat(p + "w_gate_up", (2 * I, H)),
+                "w_down": mat(p + "w_down", (H, I)),
+            })
+    return w
+
+
+def make_prompt(shape: DecoderShape, n: int, seed: int = SEED_PROMPT) -> np.ndarray:
+    gen = np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(n)]))
+    return gen.integers(0, shape.vocab, size=n, dtype=np.int64).astype(np.int32)
+
+
+def make_visual_embeds(shape: DecoderShape, n: int, seed: int = SEED_VISUAL) -> np.ndarray:
+    """`n` embedding rows ~ N(0,1) in the weight dtype: stand-in for a vision encoder's output."""
+    return normal_bits(seed, "visual", (n, shape.hidden), shape.weight_dtype, 0.0, 1.0, None)
+
+
+def make_kv_rows(shape: DecoderShape, layer: int, n_pos: int, seed: int = SEED_KV):
+    """Random K and V rows [n_pos, n_kv*d] (kv dtype bits) for cache injection tests."""
+    k = normal_bits(seed, f"k{layer}", (n_pos, shape.kv_dim), shape.kv_dtype, 0.0, 1.0, None)
+    v = normal_bits(seed, f"v{layer}", (n_pos, shape.kv_dim), shape.kv_dtype, 0.0, 1.0, None)
+    return k, v
