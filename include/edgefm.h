@@ -1,0 +1,147 @@
+/*
+ * libedgefm -- single-request (batch 1) transformer-decoder inference for AMD MI355X (gfx950).
+ *
+ * The boundary follows the paper's statement of the problem (Section 3.1: one
+ * request, token ids in, tokens out, deterministic low latency), its two-phase
+ * execution (Section 3.5, Eq. 3 prefill and Eq. 4 decode step with KV update),
+ * its fixed per-request pipeline (Section 3.7: take a pre-allocated KV slot,
+ * one prefill, decode steps, release/recycle) and its graph-replay rules
+ * (Section 3.10: everything that changes per step lives in device memory).
+ *
+ * Conventions for every entry point
+ *   - plain C ABI, no exceptions, no abort, nothing printed;
+ *   - return value: EDGEFM_OK (0) or a negative edgefm_status code;
+ *   - "dev" pointers are device (HBM) addresses owned by the caller,
+ *     "host" pointers are ordinary host memory owned by the caller;
+ *   - 16-bit tensors are raw storage bits (IEEE binary16 or bfloat16);
+ *   - one model handle is driven by one host thread at a time and enqueues all
+ *     work on the HIP stream given at load time.
+ */
+#ifndef EDGEFM_H
+#define EDGEFM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct edgefm_model edgefm_model; /* opaque, library-owned host object */
+
+typedef enum { EDGEFM_F16 = 1, EDGEFM_BF16 = 2 } edgefm_dtype;
+
+typedef enum {
+    EDGEFM_OK = 0,
+    EDGEFM_ERR_INVALID_ARG = -1,      /* NULL pointer, zero dimension, unsupported shape or dtype        */
+    EDGEFM_ERR_ARENA_TOO_SMALL = -2,  /* arena_bytes below edgefm_query_sizes()                          */
+    EDGEFM_ERR_CONTEXT_OVERFLOW = -3, /* kv_len + new positions > max_seq_len; state unchanged           */
+    EDGEFM_ERR_BAD_TOKEN = -4,        /* token id < 0 or >= vocab; checked on the host, nothing enqueued */
+    EDGEFM_ERR_STATE = -5,            /* token -1 with no previous greedy token, keep_len > kv_len, ...  */
+    EDGEFM_ERR_HIP = -6               /* a HIP call failed; see edgefm_last_hip_error()                  */
+} edgefm_status;
+
+/* Decoder shape.  Supported: head_dim 64 or 128; n_q_heads / n_kv_heads in 1..8;
+ * hidden and intermediate multiples of 8 and at most 38400; 16-bit weights. */
+typedef struct {
+    uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab;
+    uint32_t max_seq_len;          /* KV slot size, pre-allocated at load (Section 3.9) */
+    float rms_eps, rope_theta;
+    uint32_t weight_dtype, kv_dtype; /* edgefm_dtype; embeddings passed to prefill use weight_dtype */
+    uint32_t tie_embeddings;         /* 1: lm_head is the embedding matrix                           */
+    uint32_t qkv_bias;               /* 1: bqkv present                                              */
+} edgefm_config;
+
+/* Canonical parameters, DEVICE pointers, row-major [out, in], weight_dtype storage.
+ * Per-layer entries are HOST arrays of n_layers device pointers.
+ *   wqkv      [(n_q + 2 n_kv) * head_dim, hidden], rows ordered Q heads | K heads | V heads (layer role
+ *             "fused_qkv", Table 1);  bqkv [(n_q + 2 n_kv) * head_dim] or NULL table when qkv_bias == 0
+ *   wo        [hidden, n_q * head_dim]
+ *   w_gate_up [2 * intermediate, hidden], rows ordered gate | up
+ *   w_down    [hidden, intermediate]
+ *   attn_norm, mlp_norm, final_norm [hidden];  embed, lm_head [vocab, hidden] (lm_head NULL when tied)
+ * The library copies everything into the arena during edgefm_model_load; the caller may free the
+ * canonical tensors afterwards (the arena then is the deployment artifact of Section 3.5). */
+typedef struct {
+    const void *embed, *lm_head, *final_norm;
+    const void *const *attn_norm, *const *wqkv, *const *bqkv, *const *wo;
+    const void *const *mlp_norm, *const *w_gate_up, *const *w_down;
+} edgefm_weights;
+
+/* Bytes of device memory edgefm_model_load needs for this configuration (weights copy, RoPE table,
+ * KV slot of max_seq_len positions, decode and prefill scratch).  Host-only computation. */
+int edgefm_query_sizes(const edgefm_config *cfg, size_t *arena_bytes);
+
+/* Build a model (Section 3.7 "allocate KV cache slots", Section 3.9 pre-allocation at engine start).
+ *   arena_dev : caller-owned device buffer, 256-byte aligned, >= arena_bytes; must outlive the handle
+ *   hip_stream: a hipStream_t (NULL = the null stream); all later work is enqueued there
+ * On return (stream synchronised) the weights have been copied and kv_len == 0. */
+int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *weights, void *arena_dev,
+                      size_t arena_bytes, void *hip_stream, edgefm_model **out);
+
+/* Prefill (Eq. 3): append n_embeds caller-supplied embedding rows, then n_tokens token ids, to the
+ * context, positions kv_len .. kv_len + n - 1; writes their K/V into the cache (K after RoPE, rounded
+ * to kv_dtype) and returns the greedy next token (argmax of the last position's logits, lowest index
+ * on ties; Section 4.2 greedy setting).  A non-zero kv_len continues after a kept prefix (Eq. 5).
+ *   token_ids_host : [n_tokens] int32, host (may be NULL when n_tokens == 0)
+ *   embeds_dev     : [n_embeds, hidden] weight_dtype, device (may be NULL when n_embeds == 0)
+ *   logits_host    : NULL or [vocab] float, host; last position's logits
+ *   next_token_host: NULL or one int32, host
+ * Synchronises the stream before returning.  Errors leave kv_len unchanged. */
+int edgefm_prefill(edgefm_model *m, const int32_t *token_ids_host, uint32_t n_tokens, const void *embeds_dev,
+                   uint32_t n_embeds, float *logits_host, int32_t *next_token_host);
+
+/* One decode step (Eq. 4): evaluate `token` at position kv_len, append its K/V (UpdateKV), advance
+ * kv_len, and produce the next greedy token.  The step is one replay of a captured HIP graph whose
+ * per-step parameters (position, current token) live in device memory (Section 3.10).
+ *   token           : >= 0 explicit token id; -1 = the previous call's greedy token, taken on the device
+ *   logits_host     : NULL or [vocab] float
+ *   next_token_host : NULL or one int32
+ * If both host pointers are NULL the call only enqueues work and returns without synchronising, so
+ * steps chain on the device; otherwise it synchronises the stream. */
+int edgefm_decode_step(edgefm_model *m, int32_t token, float *logits_host, int32_t *next_token_host);
+
+/* Release or recycle the KV slot (Section 3.7; Section 3.9 fixed-prefix reuse): keep the first
+ * keep_len positions, forget the rest.  keep_len == 0 is a full reset.  Constant time. */
+int edgefm_kv_reset(edgefm_model *m, uint32_t keep_len);
+
+/* Number of valid context positions (host mirror of the device-side counter). */
+uint32_t edgefm_kv_len(const edgefm_model *m);
+
+/* Destroy the handle (graph objects, pinned staging).  The arena is the caller's. */
+void edgefm_model_free(edgefm_model *m);
+
+const char *edgefm_strerror(int status);
+/* hipError_t value of the last failed HIP call on this handle (0 if none). */
+int edgefm_last_hip_error(const edgefm_model *m);
+
+/* ---- test and measurement accessors (synchronise the stream) ---------------------------------- */
+
+/* Copy one cache position of one layer to the host: k, v are [n_kv_heads * head_dim] kv_dtype bits.
+ * Any pos < max_seq_len may be read (tests look for writes outside the valid range). */
+int edgefm_debug_kv_read(edgefm_model *m, uint32_t layer, uint32_t pos, void *k_host, void *v_host);
+/* Overwrite cache positions 0 .. n_pos-1 of one layer from host rows [n_pos, n_kv_heads * head_dim]. */
+int edgefm_debug_kv_write(edgefm_model *m, uint32_t layer, uint32_t n_pos, const void *k_host,
+                          const void *v_host);
+/* Fill the whole KV slot with a 16-bit pattern (sentinel for indexing tests). */
+int edgefm_debug_kv_fill(edgefm_model *m, uint16_t pattern);
+/* Declare the first n positions valid (after edgefm_debug_kv_write on every layer). */
+int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n);
+/* Final-norm output ("final hidden state") of the most recent prefill / decode step: [hidden] float. */
+int edgefm_debug_last_hidden(edgefm_model *m, float *hidden_host);
+
+/* Enqueue `repeat` launches of one decode-stage kernel on the model's stream, without synchronising
+ * (the caller brackets the call with HIP events to time a single kernel, Section 3.4 profile-guided
+ * workflow).  layer < 0 cycles through the layers so that no launch re-reads the previous one's
+ * weights.  The model's activations are overwritten with finite garbage; call edgefm_kv_reset and
+ * prefill again before using the model for inference.  Requires kv_len >= 1. */
+typedef enum {
+    EDGEFM_OP_QKV = 0, EDGEFM_OP_ATTN = 1, EDGEFM_OP_OPROJ = 2, EDGEFM_OP_GATEUP = 3, EDGEFM_OP_DOWN = 4,
+    EDGEFM_OP_LMHEAD = 5
+} edgefm_op;
+int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EDGEFM_H */

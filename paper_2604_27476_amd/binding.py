@@ -1,0 +1,248 @@
+"""Thin ctypes binding of libedgefm.so: same entry-point names as ``include/edgefm.h``.
+
+Argument marshalling only -- every step of the decoder runs in the library's HIP
+kernels.  PyTorch is used for device memory (the arena, the canonical weights,
+embedding rows) and for the HIP stream handed to the library.  If the shared
+library is missing or cannot be loaded this module raises: there is no fallback
+path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from .build import lib_path
+
+EDGEFM_F16, EDGEFM_BF16 = 1, 2
+EDGEFM_OK = 0
+EDGEFM_ERR_INVALID_ARG, EDGEFM_ERR_ARENA_TOO_SMALL, EDGEFM_ERR_CONTEXT_OVERFLOW = -1, -2, -3
+EDGEFM_ERR_BAD_TOKEN, EDGEFM_ERR_STATE, EDGEFM_ERR_HIP = -4, -5, -6
+EDGEFM_OP_QKV, EDGEFM_OP_ATTN, EDGEFM_OP_OPROJ, EDGEFM_OP_GATEUP, EDGEFM_OP_DOWN, EDGEFM_OP_LMHEAD = range(6)
+
+EXPORTS = [
+    "edgefm_query_sizes", "edgefm_model_load", "edgefm_prefill", "edgefm_decode_step", "edgefm_kv_reset",
+    "edgefm_kv_len", "edgefm_model_free", "edgefm_strerror", "edgefm_last_hip_error", "edgefm_debug_kv_read",
+    "edgefm_debug_kv_write", "edgefm_debug_kv_fill", "edgefm_debug_set_kv_len", "edgefm_debug_last_hidden",
+    "edgefm_debug_launch_op",
+]
+
+
+class edgefm_config(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim",
+                                           "intermediate", "vocab", "max_seq_len")] + \
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float)] + \
+               [(n, C.c_uint32) for n in ("weight_dtype", "kv_dtype", "tie_embeddings", "qkv_bias")]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class edgefm_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
+               [(n, _PP) for n in ("attn_norm", "wqkv", "bqkv", "wo", "mlp_norm", "w_gate_up", "w_down")]
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libedgefm.so (built in-tree by ``paper_2604_27476_amd.build()``) and declare its ABI."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = C.CDLL(path)
+    m = C.c_void_p
+    lib.edgefm_query_sizes.argtypes = [C.POINTER(edgefm_config), C.POINTER(C.c_size_t)]
+    lib.edgefm_model_load.argtypes = [C.POINTER(edgefm_config), C.POINTER(edgefm_weights), C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.edgefm_prefill.argtypes = [m, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
+    lib.edgefm_decode_step.argtypes = [m, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.edgefm_kv_reset.argtypes = [m, C.c_uint32]
+    lib.edgefm_kv_len.argtypes = [m]
+    lib.edgefm_kv_len.restype = C.c_uint32
+    lib.edgefm_model_free.argtypes = [m]
+    lib.edgefm_model_free.restype = None
+    lib.edgefm_strerror.argtypes = [C.c_int]
+    lib.edgefm_strerror.restype = C.c_char_p
+    lib.edgefm_last_hip_error.argtypes = [m]
+    lib.edgefm_debug_kv_read.argtypes = [m, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
+    lib.edgefm_debug_kv_write.argtypes = [m, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
+    lib.edgefm_debug_kv_fill.argtypes = [m, C.c_uint16]
+    lib.edgefm_debug_set_kv_len.argtypes = [m, C.c_uint32]
+    lib.edgefm_debug_last_hidden.argtypes = [m, C.c_void_p]
+    lib.edgefm_debug_launch_op.argtypes = [m, C.c_int, C.c_int, C.c_uint32]
+    for name in EXPORTS:
+        if name not in ("edgefm_kv_len", "edgefm_model_free", "edgefm_strerror"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+class EdgefmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().edgefm_strerror(status).decode()
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != EDGEFM_OK:
+        raise EdgefmError(status, where)
+
+
+def make_config(shape, max_seq_len=None, n_layers=None) -> edgefm_config:
+    """edgefm_config from a synthetic-shape record (any object with the same field names)."""
+    return edgefm_config(shape.n_layers if n_layers is None else n_layers, shape.hidden, shape.n_q_heads,
+                         shape.n_kv_heads, shape.head_dim, shape.intermediate, shape.vocab,
+                         shape.max_seq_len if max_seq_len is None else max_seq_len, shape.rms_eps, shape.rope_theta,
+                         shape.weight_dtype, shape.kv_dtype, int(shape.tie_embeddings), int(shape.qkv_bias))
+
+
+def edgefm_query_sizes(cfg: edgefm_config) -> int:
+    n = C.c_size_t(0)
+    _check(load_library().edgefm_query_sizes(C.byref(cfg), C.byref(n)), "edgefm_query_sizes")
+    return n.value
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Model:
+    """Owner of one library handle plus the torch-allocated device memory it lives in.
+
+    Methods are one-to-one with the C entry points (``prefill`` -> ``edgefm_prefill`` ...)."""
+
+    def __init__(self, cfg: edgefm_config, weights: dict, device="cuda:0", stream=None):
+        """`weights`: dict in the layout of ``synth.make_weights`` holding uint16 numpy arrays (uploaded
+        here) or torch device tensors of 16-bit element type."""
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        nbytes = edgefm_query_sizes(cfg)
+        self.arena_bytes = nbytes
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.arena.data_ptr()
+        self.arena_ptr = (base + 255) // 256 * 256
+        L = cfg.n_layers
+
+        def dev(t):
+            if t is None:
+                return None
+            if isinstance(t, np.ndarray):
+                assert t.dtype == np.uint16
+                t = torch.from_numpy(np.ascontiguousarray(t).view(np.int16)).to(self.device)
+            assert t.is_contiguous() and t.element_size() == 2
+            return t
+
+        keep = {"embed": dev(weights["embed"]), "lm_head": dev(weights["lm_head"]),
+                "final_norm": dev(weights["final_norm"]), "layers": []}
+        tables = {}
+        names = ("attn_norm", "wqkv", "bqkv", "wo", "mlp_norm", "w_gate_up", "w_down")
+        for l in range(L):
+            keep["layers"].append({k: dev(weights["layers"][l][k]) for k in names})
+        for k in names:
+            arr = (C.c_void_p * L)()
+            any_set = False
+            for l in range(L):
+                t = keep["layers"][l][k]
+                arr[l] = None if t is None else t.data_ptr()
+                any_set |= t is not None
+            tables[k] = C.cast(arr, _PP) if any_set else None
+            keep.setdefault("_tables", []).append(arr)
+        w = edgefm_weights(keep["embed"].data_ptr(), None if keep["lm_head"] is None else keep["lm_head"].data_ptr(),
+                           keep["final_norm"].data_ptr(), *[tables[k] for k in names])
+        torch.cuda.synchronize(self.device)
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            st = self.lib.edgefm_model_load(C.byref(cfg), C.byref(w), C.c_void_p(self.arena_ptr), nbytes,
+                                            C.c_void_p(self.stream.cuda_stream), C.byref(h))
+        _check(st, "edgefm_model_load")
+        self.h = h
+        del keep  # the library copied the parameters into the arena
+        self._logits = np.empty(cfg.vocab, dtype=np.float32)
+        self._next = np.zeros(1, dtype=np.int32)
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.edgefm_model_free(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the four calls of the boundary -------------------------------------------------------
+    def prefill(self, tokens=None, embeds=None, want_logits=True):
+        """edgefm_prefill.  `embeds`: uint16 numpy [n, hidden] (uploaded) or a torch device tensor."""
+        torch = self.torch
+        tok = np.zeros(0, np.int32) if tokens is None else np.ascontiguousarray(tokens, dtype=np.int32)
+        emb = None
+        n_emb = 0
+        if embeds is not None:
+            emb = embeds
+            if isinstance(emb, np.ndarray):
+                emb = torch.from_numpy(np.ascontiguousarray(emb).view(np.int16)).to(self.device)
+                torch.cuda.synchronize(self.device)
+            n_emb = emb.shape[0]
+        st = self.lib.edgefm_prefill(self.h, _np_ptr(tok) if tok.size else None, tok.size,
+                                     None if emb is None else C.c_void_p(emb.data_ptr()), n_emb,
+                                     _np_ptr(self._logits) if want_logits else None, _np_ptr(self._next))
+        _check(st, "edgefm_prefill")
+        return int(self._next[0]), (self._logits.copy() if want_logits else None)
+
+    def decode_step(self, token: int = -1, want_logits=False, sync=True):
+        """edgefm_decode_step.  sync=False enqueues only (device-chained greedy decoding)."""
+        if not sync:
+            _check(self.lib.edgefm_decode_step(self.h, token, None, None), "edgefm_decode_step")
+            return None, None
+        st = self.lib.edgefm_decode_step(self.h, token, _np_ptr(self._logits) if want_logits else None,
+                                         _np_ptr(self._next))
+        _check(st, "edgefm_decode_step")
+        return int(self._next[0]), (self._logits.copy() if want_logits else None)
+
+    def kv_reset(self, keep_len: int = 0):
+        _check(self.lib.edgefm_kv_reset(self.h, keep_len), "edgefm_kv_reset")
+
+    @property
+    def kv_len(self) -> int:
+        return self.lib.edgefm_kv_len(self.h)
+
+    # ---- test / measurement accessors ----------------------------------------------------------
+    def last_hidden(self) -> np.ndarray:
+        out = np.empty(self.cfg.hidden, dtype=np.float32)
+        _check(self.lib.edgefm_debug_last_hidden(self.h, _np_ptr(out)), "edgefm_debug_last_hidden")
+        return out
+
+    def kv_read(self, layer: int, pos: int):
+        n = self.cfg.n_kv_heads * self.cfg.head_dim
+        k = np.empty(n, dtype=np.uint16); v = np.empty(n, dtype=np.uint16)
+        _check(self.lib.edgefm_debug_kv_read(self.h, layer, pos, _np_ptr(k), _np_ptr(v)), "edgefm_debug_kv_read")
+        return k, v
+
+    def kv_write(self, layer: int, k_rows: np.ndarray, v_rows: np.ndarray):
+        k = np.ascontiguousarray(k_rows, dtype=np.uint16); v = np.ascontiguousarray(v_rows, dtype=np.uint16)
+        _check(self.lib.edgefm_debug_kv_write(self.h, layer, k.shape[0], _np_ptr(k), _np_ptr(v)),
+               "edgefm_debug_kv_write")
+
+    def kv_fill(self, pattern: int):
+        _check(self.lib.edgefm_debug_kv_fill(self.h, pattern), "edgefm_debug_kv_fill")
+
+    def set_kv_len(self, n: int):
+        _check(self.lib.edgefm_debug_set_kv_len(self.h, n), "edgefm_debug_set_kv_len")
+
+    def launch_op(self, op: int, layer: int = -1, repeat: int = 1):
+        _check(self.lib.edgefm_debug_launch_op(self.h, op, layer, repeat), "edgefm_debug_launch_op")
+
+    def synchronize(self):
+        self.stream.synchronize()

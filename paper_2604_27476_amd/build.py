@@ -1,0 +1,49 @@
+"""Compile libedgefm.so for gfx950 with hipcc (cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_DIR, "csrc")
+_SOURCES = ["model.hip", "decode_kernels.hip", "prefill_kernels.hip"]
+_HEADERS = ["common.h", "kernels.h", os.path.join("..", "..", "include", "edgefm.h")]
+
+
+def lib_path() -> str:
+    return os.path.join(_DIR, "libedgefm.so")
+
+
+def _stale() -> bool:
+    out = lib_path()
+    if not os.path.exists(out):
+        return True
+    t = os.path.getmtime(out)
+    return any(os.path.getmtime(os.path.join(_CSRC, f)) > t for f in _SOURCES + _HEADERS)
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    """Build the library in-tree.  ``force=False`` rebuilds only when a source is newer."""
+    out = lib_path()
+    if not force and not _stale():
+        return out
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objs = []
+    procs = []
+    for src in _SOURCES:
+        obj = os.path.join(_CSRC, src.replace(".hip", ".o"))
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wall", "-Wno-unused-function", "-c", os.path.join(_CSRC, src), "-o", obj]
+        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for cmd, p in procs:
+        log, _ = p.communicate()
+        log = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l)
+        if p.returncode != 0:
+            raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + log)
+        if verbose and log.strip():
+            print(log)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs
+    subprocess.run(link, check=True)
+    return out

@@ -1,0 +1,96 @@
+// Device-side helpers shared by the decode and prefill kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace efm {
+
+constexpr int DT_F16 = 1;   // IEEE binary16 storage
+constexpr int DT_BF16 = 2;  // bfloat16 storage
+constexpr int WAVE = 64;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
+
+// ---- 16-bit storage <-> fp32 (exact upcast; round-to-nearest-even downcast) -------------------
+template <int DT> __device__ __forceinline__ float up1(uint16_t b) {
+    if constexpr (DT == DT_BF16) {
+        return as_f32((uint32_t)b << 16);
+    } else {
+        _Float16 h;
+        __builtin_memcpy(&h, &b, 2);
+        return (float)h;
+    }
+}
+
+// two packed 16-bit values (low half first) -> two floats
+template <int DT> __device__ __forceinline__ void up2(uint32_t w, float &lo, float &hi) {
+    if constexpr (DT == DT_BF16) {
+        lo = as_f32(w << 16);
+        hi = as_f32(w & 0xffff0000u);
+    } else {
+        f16x2 h;
+        __builtin_memcpy(&h, &w, 4);
+        lo = (float)h.x;
+        hi = (float)h.y;
+    }
+}
+
+template <int DT> __device__ __forceinline__ void unpack8(const u32x4 &v, float *f) {
+    up2<DT>(v.x, f[0], f[1]);
+    up2<DT>(v.y, f[2], f[3]);
+    up2<DT>(v.z, f[4], f[5]);
+    up2<DT>(v.w, f[6], f[7]);
+}
+
+template <int DT> __device__ __forceinline__ uint16_t down1(float f) {
+    if constexpr (DT == DT_BF16) {
+        uint32_t u = as_u32(f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+        u += 0x7fffu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    } else {
+        _Float16 h = (_Float16)f;  // v_cvt_f16_f32, round to nearest even
+        uint16_t b;
+        __builtin_memcpy(&b, &h, 2);
+        return b;
+    }
+}
+
+template <int DT> __device__ __forceinline__ uint32_t down2(float lo, float hi) {
+    return (uint32_t)down1<DT>(lo) | ((uint32_t)down1<DT>(hi) << 16);
+}
+
+// ---- loads ---------------------------------------------------------------------------------------
+// 128-bit streaming load: weights are read exactly once per step, so they should not displace the
+// activations and KV tiles that live in L2.
+__device__ __forceinline__ u32x4 ld_stream16(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+__device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+
+// ---- wave / block reductions -------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// Sum over the whole block (blockDim.x multiple of 64, at most 1024). `red` is LDS scratch of >= 17
+// floats.  Every thread gets the result; the summation order is fixed, so results are reproducible.
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();  // red may still be read from a previous use
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < nw; ++i) t += red[i];
+    return t;
+}
+
+}  // namespace efm

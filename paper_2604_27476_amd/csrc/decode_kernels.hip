@@ -1,0 +1,602 @@
+// Decode-step kernels (m = 1; Eq. 4 of Section 3.5): every linear layer is a GEMV that streams its
+// weights once from HBM with 128-bit loads; normalisation, bias, RoPE, the KV-cache write, SwiGLU and
+// the residual adds are fused into GEMV prologues/epilogues (the operator list of Section 3.4).
+// Everything that changes from step to step (position, token) is read from device memory so that the
+// whole step can be replayed as one captured graph (Section 3.10).
+#include "common.h"
+#include "kernels.h"
+
+namespace efm {
+
+// ------------------------------------------------------------------------------------------------
+// Activation vector staged in LDS.  Layout: two float4 arrays of nvec = n/8 entries,
+//   lo[v] = x[8v .. 8v+3], hi[v] = x[8v+4 .. 8v+7],
+// so that lane i of a wave reads lo[v0+i] / hi[v0+i]: consecutive 16-byte words, no bank conflicts.
+// With NORM the staged vector is RMSNorm(x) * gain.
+// ------------------------------------------------------------------------------------------------
+template <int DT, bool NORM>
+__device__ __forceinline__ void stage_vec(const float *__restrict__ x, const uint16_t *__restrict__ gain, int n,
+                                          float eps, float4 *xs, float *red) {
+    const int nvec = n >> 3;
+    float rstd = 1.f;
+    if constexpr (NORM) {
+        float ss = 0.f;
+        for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+            const float4 a = reinterpret_cast<const float4 *>(x)[2 * v];
+            const float4 b = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+        }
+        ss = block_sum(ss, red);
+        rstd = 1.0f / sqrtf(ss / (float)n + eps);
+    }
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        float4 a = reinterpret_cast<const float4 *>(x)[2 * v];
+        float4 b = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+        if constexpr (NORM) {
+            float g[8];
+            unpack8<DT>(ld16(gain + 8 * v), g);
+            a.x = a.x * rstd * g[0]; a.y = a.y * rstd * g[1]; a.z = a.z * rstd * g[2]; a.w = a.w * rstd * g[3];
+            b.x = b.x * rstd * g[4]; b.y = b.y * rstd * g[5]; b.z = b.z * rstd * g[6]; b.w = b.w * rstd * g[7];
+        }
+        xs[v] = a;
+        xs[nvec + v] = b;
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------------
+// One wave computes NR dot products of length K = 8*nvec against the staged vector.
+// Each lane keeps up to U*NR independent 16-byte loads in flight before the FMA chain.
+// ------------------------------------------------------------------------------------------------
+template <int DT, int NR, int U>
+__device__ __forceinline__ void wave_dots(const uint16_t *const (&rows)[NR], const float4 *xs, int nvec, int lane,
+                                          float (&out)[NR]) {
+    float acc[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) acc[r] = 0.f;
+    for (int v0 = lane; v0 < nvec; v0 += WAVE * U) {
+        u32x4 w[U][NR];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * WAVE;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                if (v < nvec) w[u][r] = ld_stream16(rows[r] + (size_t)v * 8);
+                else w[u][r] = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * WAVE;
+            if (v < nvec) {
+                const float4 a = xs[v], b = xs[nvec + v];
+#pragma unroll
+                for (int r = 0; r < NR; ++r) {
+                    float f[8];
+                    unpack8<DT>(w[u][r], f);
+                    float s = acc[r];
+                    s = fmaf(f[0], a.x, s); s = fmaf(f[1], a.y, s); s = fmaf(f[2], a.z, s); s = fmaf(f[3], a.w, s);
+                    s = fmaf(f[4], b.x, s); s = fmaf(f[5], b.y, s); s = fmaf(f[6], b.z, s); s = fmaf(f[7], b.w, s);
+                    acc[r] = s;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) out[r] = wave_sum(acc[r]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// embed: x <- upcast(E[token])
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void k_embed(const uint16_t *__restrict__ E, const int *__restrict__ d_token, float *__restrict__ x,
+                        int H) {
+    const int tok = d_token[0];
+    const uint16_t *row = E + (size_t)tok * H;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < H; i += gridDim.x * blockDim.x) x[i] = up1<DT>(row[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// fused QKV: RMSNorm prologue, GEMV, bias + RoPE + KV-cache write epilogue (layer role "fused_qkv").
+// A work unit is the pair of rows (i, i + d/2) of one head: the two partners of the rotation
+// y_i = x_i cos - x_{i+d/2} sin, y_{i+d/2} = x_{i+d/2} cos + x_i sin (slice / negate / concat form of
+// Appendix B.3).  V heads use the same pairing without rotation.
+// ------------------------------------------------------------------------------------------------
+template <int DT, int KDT>
+__global__ void __launch_bounds__(1024)
+k_qkv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const uint16_t *__restrict__ gain,
+      const float *__restrict__ x, const float *__restrict__ rope_cos, const float *__restrict__ rope_sin,
+      const int *__restrict__ d_pos, float *__restrict__ q, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
+      int H, int nq, int nkv, int d, int max_seq, float eps) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    stage_vec<DT, true>(x, gain, H, eps, smem, red);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int half = d >> 1, n_units = (nq + 2 * nkv) * half, nvec = H >> 3;
+    const int pos = d_pos[0];
+    for (int unit = blockIdx.x * nw + wave; unit < n_units; unit += gridDim.x * nw) {
+        const int hh = unit / half, i = unit - hh * half;
+        const int r0 = hh * d + i, r1 = r0 + half;
+        const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)r1 * H};
+        float o[2];
+        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        if (lane == 0) {
+            float v0 = o[0], v1 = o[1];
+            if (bias) {
+                v0 += up1<DT>(bias[r0]);
+                v1 += up1<DT>(bias[r1]);
+            }
+            if (hh < nq + nkv) {
+                const float c = rope_cos[(size_t)pos * half + i], s = rope_sin[(size_t)pos * half + i];
+                const float y0 = v0 * c - v1 * s, y1 = v1 * c + v0 * s;
+                v0 = y0;
+                v1 = y1;
+            }
+            if (hh < nq) {
+                q[r0] = v0;
+                q[r1] = v1;
+            } else if (hh < nq + nkv) {
+                uint16_t *dst = kc + ((size_t)(hh - nq) * max_seq + pos) * d;
+                dst[i] = down1<KDT>(v0);
+                dst[i + half] = down1<KDT>(v1);
+            } else {
+                uint16_t *dst = vc + ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
+                dst[i] = down1<KDT>(v0);
+                dst[i + half] = down1<KDT>(v1);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// x[r] += W[r] . vec  (O projection and down projection with the residual add in the epilogue)
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(1024)
+k_gemv_resid(const uint16_t *__restrict__ W, const float *__restrict__ vec, float *__restrict__ x, int rows_n,
+             int K) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    stage_vec<DT, false>(vec, nullptr, K, 0.f, smem, red);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int n_units = (rows_n + 1) >> 1, nvec = K >> 3;
+    for (int unit = blockIdx.x * nw + wave; unit < n_units; unit += gridDim.x * nw) {
+        const int r0 = 2 * unit, r1 = min(2 * unit + 1, rows_n - 1);
+        const uint16_t *rows[2] = {W + (size_t)r0 * K, W + (size_t)r1 * K};
+        float o[2];
+        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        if (lane == 0) {
+            x[r0] += o[0];
+            if (r1 != r0) x[r1] += o[1];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// gate/up GEMV with RMSNorm prologue and SwiGLU epilogue: unit j = rows (j, I + j)
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(1024)
+k_gateup(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
+         float *__restrict__ h, int H, int I, float eps) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    stage_vec<DT, true>(x, gain, H, eps, smem, red);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int nvec = H >> 3;
+    for (int j = blockIdx.x * nw + wave; j < I; j += gridDim.x * nw) {
+        const uint16_t *rows[2] = {W + (size_t)j * H, W + (size_t)(I + j) * H};
+        float o[2];
+        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        if (lane == 0) h[j] = o[0] / (1.0f + expf(-o[0])) * o[1];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// lm_head GEMV with final-RMSNorm prologue; logits are stored and each block keeps its (max, lowest
+// index) so that greedy sampling needs no second pass over the logits.
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(1024)
+k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
+         float *__restrict__ logits, float *__restrict__ hidden, float *__restrict__ part_val,
+         int *__restrict__ part_idx, int H, int V, float eps) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    stage_vec<DT, true>(x, gain, H, eps, smem, red);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int nvec = H >> 3;
+    if (blockIdx.x == 0) {  // export the final hidden state (the tensor the parity tolerance is stated on)
+        for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+            reinterpret_cast<float4 *>(hidden)[2 * v] = smem[v];
+            reinterpret_cast<float4 *>(hidden)[2 * v + 1] = smem[nvec + v];
+        }
+    }
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    const int n_units = (V + 1) >> 1;
+    for (int unit = blockIdx.x * nw + wave; unit < n_units; unit += gridDim.x * nw) {
+        const int r0 = 2 * unit, r1 = min(2 * unit + 1, V - 1);
+        const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)r1 * H};
+        float o[2];
+        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        if (lane == 0) {
+            logits[r0] = o[0];
+            if (o[0] > best) { best = o[0]; best_i = r0; }   // rows visited in increasing order per wave
+            if (r1 != r0) {
+                logits[r1] = o[1];
+                if (o[1] > best) { best = o[1]; best_i = r1; }
+            }
+        }
+    }
+    if (lane == 0) {
+        bv[wave] = best;
+        bi[wave] = best_i;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < nw; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < best_i)) { best = bv[w]; best_i = bi[w]; }
+        part_val[blockIdx.x] = best;
+        part_idx[blockIdx.x] = best_i;
+    }
+}
+
+// finish: greedy token = argmax over the per-block partials (lowest index on ties); feed it back as
+// the next step's input token and advance the position (the "KV cache management kernel" of
+// Section 3.10 that keeps the decode step a fixed graph).
+__global__ void k_finish(const float *__restrict__ part_val, const int *__restrict__ part_idx, int n_part,
+                         int *__restrict__ d_next, int *__restrict__ d_token, int *__restrict__ d_pos, int advance) {
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    for (int p = threadIdx.x; p < n_part; p += blockDim.x) {
+        const float v = part_val[p];
+        const int i = part_idx[p];
+        if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
+    }
+    sv[threadIdx.x] = best;
+    si[threadIdx.x] = best_i;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int t = 1; t < (int)blockDim.x; ++t)
+            if (sv[t] > best || (sv[t] == best && si[t] < best_i)) { best = sv[t]; best_i = si[t]; }
+        if (best_i == 0x7fffffff) best_i = 0;  // all logits NaN/-inf: still return a valid id
+        d_next[0] = best_i;
+        d_token[0] = best_i;
+        d_pos[0] += advance;
+    }
+}
+
+__global__ void k_set_int(int *p, int v) { p[0] = v; }
+__global__ void k_fill_u16(uint16_t *p, size_t n, uint16_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Decode attention (GQA, single query per head): grid (splits, n_kv).  A workgroup serves all GQ query
+// heads of one KV head over one slice of the context, so every K/V row is fetched once.  A row of D
+// 16-bit values is covered by LPR = D/8 lanes with one 16-byte load each; a wave therefore processes
+// 64/LPR rows per load instruction, UR instructions deep.  Each lane group keeps an online-softmax
+// state (max, sum, weighted V) per head; the groups of a wave are merged with shuffles, the waves
+// through LDS, the context slices by the last workgroup to arrive (fixed order: reproducible).
+// Scores use a finite sentinel instead of -inf (Appendix B.3, item 3).
+// ------------------------------------------------------------------------------------------------
+constexpr float NEG_BIG = -1.0e30f;
+constexpr int ATTN_CHUNK_MIN = 64;
+
+template <int KDT, int D, int GQ>
+__global__ void __launch_bounds__(256)
+k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
+              const int *__restrict__ d_pos, float *__restrict__ part, uint32_t *__restrict__ counters,
+              float *__restrict__ o, int max_seq, int S, float scale) {
+    constexpr int LPR = D / 8;       // lanes per row
+    constexpr int RW = WAVE / LPR;   // rows per wave per load
+    constexpr int UR = 4;            // loads in flight per lane (K and V each)
+    constexpr int NW = 4;
+    constexpr int PS = D + 2;        // partial record: m, l, acc[D]
+    __shared__ float wstate[NW][GQ][PS];
+    __shared__ uint32_t ticket_s;
+
+    const int kvh = blockIdx.y, s = blockIdx.x;
+    const int n_keys = d_pos[0] + 1;
+    int chunk = (n_keys + S - 1) / S;
+    if (chunk < ATTN_CHUNK_MIN) chunk = ATTN_CHUNK_MIN;
+    const int n_active = (n_keys + chunk - 1) / chunk;
+    if (s >= n_active) return;
+    const int j0 = s * chunk, j1 = min(n_keys, j0 + chunk);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane / LPR, li = lane % LPR;
+
+    float qr[GQ][8];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        const float *qp = q + (size_t)(kvh * GQ + h) * D + li * 8;
+        const float4 a = reinterpret_cast<const float4 *>(qp)[0], b = reinterpret_cast<const float4 *>(qp)[1];
+        qr[h][0] = a.x * scale; qr[h][1] = a.y * scale; qr[h][2] = a.z * scale; qr[h][3] = a.w * scale;
+        qr[h][4] = b.x * scale; qr[h][5] = b.y * scale; qr[h][6] = b.z * scale; qr[h][7] = b.w * scale;
+    }
+    float m[GQ], l[GQ], acc[GQ][8];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        m[h] = NEG_BIG;
+        l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+    }
+    const uint16_t *kbase = kc + (size_t)kvh * max_seq * D + li * 8;
+    const uint16_t *vbase = vc + (size_t)kvh * max_seq * D + li * 8;
+
+    for (int jb = j0 + wave * (RW * UR); jb < j1; jb += NW * RW * UR) {
+        u32x4 kv[UR], vv[UR];
+        bool ok[UR];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            const int j = jb + u * RW + sub;
+            ok[u] = j < j1;
+            const int jj = ok[u] ? j : j0;  // any valid row; its score is discarded
+            kv[u] = ld16(kbase + (size_t)jj * D);
+            vv[u] = ld16(vbase + (size_t)jj * D);
+        }
+        float sc[UR][GQ];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            float kf[8];
+            unpack8<KDT>(kv[u], kf);
+#pragma unroll
+            for (int h = 0; h < GQ; ++h) {
+                float t = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t = fmaf(qr[h][e], kf[e], t);
+#pragma unroll
+                for (int off = LPR / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, WAVE);
+                sc[u][h] = ok[u] ? t : NEG_BIG;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) {
+            float mn = m[h];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) mn = fmaxf(mn, sc[u][h]);
+            const float corr = __expf(m[h] - mn);  // m = NEG_BIG, mn finite -> 0; both NEG_BIG -> 1 (state is 0)
+            m[h] = mn;
+            l[h] *= corr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+#pragma unroll
+            for (int u = 0; u < UR; ++u) sc[u][h] = ok[u] ? __expf(sc[u][h] - mn) : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            float vf[8];
+            unpack8<KDT>(vv[u], vf);
+#pragma unroll
+            for (int h = 0; h < GQ; ++h) {
+                const float p = sc[u][h];
+                l[h] += p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
+            }
+        }
+    }
+
+    // merge the RW lane groups of this wave (lanes with equal li)
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        float mw = m[h];
+#pragma unroll
+        for (int off = LPR; off < WAVE; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off, WAVE));
+        const float c = __expf(m[h] - mw);
+        float lw = l[h] * c;
+#pragma unroll
+        for (int off = LPR; off < WAVE; off <<= 1) lw += __shfl_xor(lw, off, WAVE);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float a = acc[h][e] * c;
+#pragma unroll
+            for (int off = LPR; off < WAVE; off <<= 1) a += __shfl_xor(a, off, WAVE);
+            acc[h][e] = a;
+        }
+        if (sub == 0) {
+            if (li == 0) {
+                wstate[wave][h][0] = mw;
+                wstate[wave][h][1] = lw;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wstate[wave][h][2 + li * 8 + e] = acc[h][e];
+        }
+    }
+    __syncthreads();
+    // merge the waves: thread (h, i) -> partial record of this context slice
+    float *prec = part + ((size_t)(kvh * GQ) * S + s) * PS;  // record of head h at + h*S*PS
+    for (int idx = threadIdx.x; idx < GQ * D; idx += blockDim.x) {
+        const int h = idx / D, i = idx - h * D;
+        float mt = wstate[0][h][0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) mt = fmaxf(mt, wstate[w][h][0]);
+        float lt = 0.f, at = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float c = __expf(wstate[w][h][0] - mt);
+            lt += wstate[w][h][1] * c;
+            at += wstate[w][h][2 + i] * c;
+        }
+        float *rec = prec + (size_t)h * S * PS;
+        if (i == 0) {
+            rec[0] = mt;
+            rec[1] = lt;
+        }
+        rec[2 + i] = at;
+    }
+    // last slice to finish merges all slices of this KV head
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0)
+        ticket_s = __hip_atomic_fetch_add(&counters[kvh], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket_s != (uint32_t)(n_active - 1)) return;
+    __threadfence();
+    for (int idx = threadIdx.x; idx < GQ * D; idx += blockDim.x) {
+        const int h = idx / D, i = idx - h * D;
+        const float *rec = part + ((size_t)(kvh * GQ + h) * S) * PS;
+        float mt = NEG_BIG;
+        for (int t = 0; t < n_active; ++t) mt = fmaxf(mt, __builtin_nontemporal_load(rec + (size_t)t * PS));
+        float lt = 0.f, at = 0.f;
+        for (int t = 0; t < n_active; ++t) {
+            const float c = __expf(__builtin_nontemporal_load(rec + (size_t)t * PS) - mt);
+            lt += __builtin_nontemporal_load(rec + (size_t)t * PS + 1) * c;
+            at += __builtin_nontemporal_load(rec + (size_t)t * PS + 2 + i) * c;
+        }
+        o[(size_t)(kvh * GQ + h) * D + i] = at / lt;
+    }
+    if (threadIdx.x == 0) counters[kvh] = 0;  // ready for the next launch (stream order)
+}
+
+// ================================================================================================
+// launchers
+// ================================================================================================
+static inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// Geometry of a row-streaming GEMV: about one workgroup per CU, each wave owning whole work units.
+struct GemvGrid {
+    int blocks, threads;
+};
+static GemvGrid gemv_grid(int n_units, int n_cu, size_t lds_bytes) {
+    int per_cu = (n_units + n_cu - 1) / n_cu;
+    int waves = clampi(per_cu, 4, 16);
+    (void)lds_bytes;
+    int blocks = (n_units + waves - 1) / waves;
+    // many units per CU: two workgroups per CU, each wave loops
+    if (blocks > 2 * n_cu) blocks = 2 * n_cu;
+    GemvGrid g = {blocks, waves * 64};
+    return g;
+}
+
+#define DT_SWITCH(dt, ...)                          \
+    if ((dt) == DT_BF16) {                          \
+        constexpr int DT = DT_BF16;                 \
+        __VA_ARGS__                                 \
+    } else {                                        \
+        constexpr int DT = DT_F16;                  \
+        __VA_ARGS__                                 \
+    }
+
+// Staged vectors longer than 64 KB (the down projection of the larger shapes) need the kernel's
+// dynamic-LDS ceiling raised once before the first launch.
+hipError_t kernels_prepare(const Dims &D) {
+    size_t need = (size_t)(D.H > D.I ? D.H : D.I) * 4;
+    if ((size_t)D.qd() * 4 > need) need = (size_t)D.qd() * 4;
+    const int n = (int)need;
+    hipError_t e;
+#define PREP(K)                                                                                              \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, n); \
+    if (e != hipSuccess) return e;
+    PREP(k_gemv_resid<DT_BF16>)
+    PREP(k_gemv_resid<DT_F16>)
+    PREP(k_gateup<DT_BF16>)
+    PREP(k_gateup<DT_F16>)
+    PREP(k_lmhead<DT_BF16>)
+    PREP(k_lmhead<DT_F16>)
+    PREP((k_qkv<DT_BF16, DT_BF16>))
+    PREP((k_qkv<DT_BF16, DT_F16>))
+    PREP((k_qkv<DT_F16, DT_BF16>))
+    PREP((k_qkv<DT_F16, DT_F16>))
+#undef PREP
+    return hipSuccess;
+}
+
+void launch_embed(const Dims &D, const uint16_t *embed, const int *d_token, float *x, hipStream_t st) {
+    const int blocks = (D.H + 255) / 256;
+    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_embed<DT>, dim3(blocks), dim3(256), 0, st, embed, d_token, x, D.H);)
+}
+
+void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, const float *rope_cos,
+                const float *rope_sin, const int *d_pos, float *q, uint16_t *kc, uint16_t *vc, hipStream_t st) {
+    const size_t lds = (size_t)D.H * 4;
+    const GemvGrid g = gemv_grid(D.R() / 2, G.n_cu, lds);
+    const uint16_t *bias = D.qkv_bias ? W.bqkv : nullptr;
+#define QKV_LAUNCH(WDT, KDT)                                                                                     \
+    hipLaunchKernelGGL((k_qkv<WDT, KDT>), dim3(g.blocks), dim3(g.threads), lds, st, W.wqkv, bias, W.attn_norm, x, \
+                       rope_cos, rope_sin, d_pos, q, kc, vc, D.H, D.nq, D.nkv, D.d, D.max_seq, D.eps)
+    if (D.wdt == DT_BF16 && D.kvdt == DT_BF16) QKV_LAUNCH(DT_BF16, DT_BF16);
+    else if (D.wdt == DT_BF16) QKV_LAUNCH(DT_BF16, DT_F16);
+    else if (D.kvdt == DT_BF16) QKV_LAUNCH(DT_F16, DT_BF16);
+    else QKV_LAUNCH(DT_F16, DT_F16);
+#undef QKV_LAUNCH
+}
+
+void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, const float *vec, float *x,
+                       hipStream_t st) {
+    const size_t lds = (size_t)K * 4;
+    const GemvGrid g = gemv_grid((D.H + 1) / 2, G.n_cu, lds);
+    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_gemv_resid<DT>, dim3(g.blocks), dim3(g.threads), lds, st, W, vec, x, D.H, K);)
+}
+
+void launch_gateup(const Dims &D, const Geo &G, const LayerW &W, const float *x, float *h, hipStream_t st) {
+    const size_t lds = (size_t)D.H * 4;
+    const GemvGrid g = gemv_grid(D.I, G.n_cu, lds);
+    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_gateup<DT>, dim3(g.blocks), dim3(g.threads), lds, st, W.w_gate_up,
+                                        W.mlp_norm, x, h, D.H, D.I, D.eps);)
+}
+
+int lmhead_blocks(const Dims &D, const Geo &G) {
+    return gemv_grid((D.V + 1) / 2, G.n_cu, (size_t)D.H * 4).blocks;
+}
+
+void launch_lmhead(const Dims &D, const Geo &G, const uint16_t *lm, const uint16_t *final_norm, const float *x,
+                   float *logits, float *hidden, float *part_val, int *part_idx, int *n_part, hipStream_t st) {
+    const size_t lds = (size_t)D.H * 4;
+    const GemvGrid g = gemv_grid((D.V + 1) / 2, G.n_cu, lds);
+    *n_part = g.blocks;
+    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_lmhead<DT>, dim3(g.blocks), dim3(g.threads), lds, st, lm, final_norm, x,
+                                        logits, hidden, part_val, part_idx, D.H, D.V, D.eps);)
+}
+
+void launch_finish(const float *part_val, const int *part_idx, int n_part, int *d_next, int *d_token, int *d_pos,
+                   int advance, hipStream_t st) {
+    hipLaunchKernelGGL(k_finish, dim3(1), dim3(256), 0, st, part_val, part_idx, n_part, d_next, d_token, d_pos,
+                       advance);
+}
+
+void launch_set_int(int *p, int v, hipStream_t st) { hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, st, p, v); }
+
+void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st) {
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_u16, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+}
+
+template <int KDT, int DD>
+static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
+                          const int *d_pos, float *part, uint32_t *counters, float *o, hipStream_t st) {
+    const dim3 grid(G.attn_splits, D.nkv), block(256);
+    const float scale = 1.0f / sqrtf((float)D.d);
+#define ATTN_CASE(GQ)                                                                                          \
+    case GQ:                                                                                                   \
+        hipLaunchKernelGGL((k_attn_decode<KDT, DD, GQ>), grid, block, 0, st, q, kc, vc, d_pos, part, counters, o, \
+                           D.max_seq, G.attn_splits, scale);                                                   \
+        break;
+    switch (D.g()) {
+        ATTN_CASE(1) ATTN_CASE(2) ATTN_CASE(3) ATTN_CASE(4) ATTN_CASE(5) ATTN_CASE(6) ATTN_CASE(7) ATTN_CASE(8)
+        default: break;
+    }
+#undef ATTN_CASE
+}
+
+void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
+                        const int *d_pos, float *part, uint32_t *counters, float *o, hipStream_t st) {
+    if (D.kvdt == DT_BF16) {
+        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, st);
+        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, st);
+    } else {
+        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, st);
+        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, st);
+    }
+}
+
+}  // namespace efm

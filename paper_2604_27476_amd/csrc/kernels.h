@@ -1,0 +1,85 @@
+// Host-callable launchers of the gfx950 kernels.  Every launcher only enqueues work on `st`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace efm {
+
+struct Dims {
+    int L, H, nq, nkv, d, I, V, max_seq;
+    int wdt, kvdt;  // DT_F16 / DT_BF16
+    int qkv_bias;
+    float eps;
+    int qd() const { return nq * d; }
+    int kvd() const { return nkv * d; }
+    int R() const { return (nq + 2 * nkv) * d; }
+    int g() const { return nq / nkv; }
+};
+
+// Per-layer device pointers (into the arena).
+struct LayerW {
+    const uint16_t *attn_norm, *wqkv, *bqkv, *wo, *mlp_norm, *w_gate_up, *w_down;
+};
+
+// Launch geometry derived once from the device's CU count.
+struct Geo {
+    int n_cu;
+    int attn_splits;  // context splits of the decode attention grid
+};
+
+hipError_t kernels_prepare(const Dims &D);
+
+// ------------------------------------------------------------------ decode (m = 1)
+// x <- upcast(E[token]) ; token read from device memory
+void launch_embed(const Dims &D, const uint16_t *embed, const int *d_token, float *x, hipStream_t st);
+// q, K[l][.,pos], V[l][.,pos] <- RoPE(Wqkv RMSNorm(x) + b) ; pos read from device memory
+void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, const float *rope_cos,
+                const float *rope_sin, const int *d_pos, float *q, uint16_t *kcache_l, uint16_t *vcache_l,
+                hipStream_t st);
+// o <- softmax(q K^T / sqrt(d)) V over cache rows 0..pos, split over the context and merged
+void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kcache_l,
+                        const uint16_t *vcache_l, const int *d_pos, float *part, uint32_t *counters, float *o,
+                        hipStream_t st);
+// x <- x + W vec   (O projection: vec = o, K = n_q d;  down projection: vec = h, K = I)
+void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, const float *vec, float *x,
+                       hipStream_t st);
+// h <- silu(Wg RMSNorm(x)) * (Wu RMSNorm(x))
+void launch_gateup(const Dims &D, const Geo &G, const LayerW &W, const float *x, float *h, hipStream_t st);
+// logits <- Wlm RMSNorm(x) ; hidden <- RMSNorm(x) ; per-block (max, index) partials
+void launch_lmhead(const Dims &D, const Geo &G, const uint16_t *lm, const uint16_t *final_norm, const float *x,
+                   float *logits, float *hidden, float *part_val, int *part_idx, int *n_part, hipStream_t st);
+// next <- argmax (lowest index on ties); token <- next; pos <- pos + advance
+void launch_finish(const float *part_val, const int *part_idx, int n_part, int *d_next, int *d_token, int *d_pos,
+                   int advance, hipStream_t st);
+void launch_set_int(int *p, int v, hipStream_t st);
+void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st);
+int lmhead_blocks(const Dims &D, const Geo &G);
+
+// ------------------------------------------------------------------ prefill (m = T)
+// Activations reach the matrix cores as a sum of 16-bit terms (see prefill_kernels.hip): GEMM A operands are
+// f16 pairs (hi, lo); the rotated query is NS terms of the cache dtype (3 for bf16, 2 for f16), term s at
+// Qs + s * q_stride.
+// X[t] <- upcast(embeds[t]) for t < n_embeds, upcast(E[tok[t - n_embeds]]) after
+void launch_embed_rows(const Dims &D, const uint16_t *embed, const uint16_t *embeds, int n_embeds, const int *tok,
+                       int n_tokens, float *X, hipStream_t st);
+// A_hi[t] + A_lo[t] <- RMSNorm(X[t]) * gain
+void launch_rmsnorm_rows(const Dims &D, const float *X, const uint16_t *gain, int T, uint16_t *Ahi, uint16_t *Alo,
+                         hipStream_t st);
+// dst <- f16(src * 2^8): the prefill copy of a weight tensor (n elements, multiple of 8)
+void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, size_t n, hipStream_t st);
+enum GemmEpi { EPI_BIAS_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+// C = (A_hi + A_lo)[T,K] W16[N,K]^T / 2^8 with an epilogue:
+//   EPI_BIAS_F32: out_f32[T,N] = C + bias      EPI_RESID: X[T,N] += C
+//   EPI_SWIGLU  : W16 is [2 I, K] (gate | up), out_hi + out_lo [T,I] = silu(C_gate) * C_up, N = I
+void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
+                 int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, hipStream_t st);
+// RoPE + cache write for positions p0..p0+T-1; sum_s Qs[s][t] = RoPE(q_t)
+void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
+                    uint16_t *Qs, size_t q_stride, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);
+// Vt[kvh][i][j] <- V[l][kvh][j][i] for j < ctx (row stride ctx_pad)
+void launch_transpose_v(const Dims &D, const uint16_t *vcache_l, int ctx, int ctx_pad, uint16_t *Vt, hipStream_t st);
+// causal GQA flash attention for queries p0..p0+T-1 over keys 0..p0+t; output as an f16 pair
+void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *kcache_l, const uint16_t *Vt,
+                       int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st);
+
+}  // namespace efm

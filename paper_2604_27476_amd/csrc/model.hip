@@ -1,0 +1,569 @@
+// Host runtime of libedgefm: the "thin runtime" of Section 3.2 -- it owns no device memory, lays the
+// caller's arena out once, and issues a fixed kernel sequence per phase (Section 3.5).  The decode step
+// is captured into a HIP graph on first use and replayed afterwards (Section 3.10).
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/edgefm.h"
+#include "common.h"
+#include "kernels.h"
+
+using namespace efm;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {
+    // offsets into the arena (bytes)
+    size_t embed, lm_head, final_norm;
+    std::vector<size_t> attn_norm, wqkv, bqkv, wo, mlp_norm, w_gate_up, w_down;
+    std::vector<size_t> p_wqkv, p_wo, p_w_gate_up, p_w_down;  // f16 prefill copies (theta_p)
+    size_t rope_cos, rope_sin, kcache, vcache;
+    // decode scratch
+    size_t x, q, o, h, part, counters, logits, hidden, part_val, part_idx, ints;
+    // prefill scratch
+    size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Vt, tok;
+    size_t total;
+};
+
+constexpr int ATTN_SPLITS = 64;
+constexpr int MAX_PARTIALS = 4096;
+
+struct Sizes {
+    size_t layer_kv;  // elements of one layer of K (or V)
+};
+
+bool valid_config(const edgefm_config *c) {
+    if (!c) return false;
+    if (!c->n_layers || !c->hidden || !c->n_q_heads || !c->n_kv_heads || !c->intermediate || !c->vocab ||
+        !c->max_seq_len)
+        return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    const uint32_t g = c->n_q_heads / c->n_kv_heads;
+    if (g < 1 || g > 8) return false;
+    if (c->hidden % 8 || c->intermediate % 8) return false;
+    if ((c->weight_dtype != EDGEFM_F16 && c->weight_dtype != EDGEFM_BF16) ||
+        (c->kv_dtype != EDGEFM_F16 && c->kv_dtype != EDGEFM_BF16))
+        return false;
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return false;
+    // staged activation vectors must fit the 160 KB LDS of a CU with room for reduction scratch
+    if ((size_t)c->hidden * 4 > 150 * 1024 || (size_t)c->intermediate * 4 > 150 * 1024 ||
+        (size_t)c->n_q_heads * c->head_dim * 4 > 150 * 1024)
+        return false;
+    if (c->max_seq_len > (1u << 20) || c->vocab > (1u << 30)) return false;
+    return true;
+}
+
+void make_layout(const edgefm_config *c, Layout &L) {
+    const size_t H = c->hidden, I = c->intermediate, V = c->vocab, d = c->head_dim;
+    const size_t qd = (size_t)c->n_q_heads * d, kvd = (size_t)c->n_kv_heads * d, R = qd + 2 * kvd;
+    const size_t Tm = c->max_seq_len, nl = c->n_layers;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes);
+        return o;
+    };
+    L.embed = take(V * H * 2);
+    L.lm_head = c->tie_embeddings ? L.embed : take(V * H * 2);
+    L.final_norm = take(H * 2);
+    L.attn_norm.resize(nl); L.wqkv.resize(nl); L.bqkv.resize(nl); L.wo.resize(nl);
+    L.mlp_norm.resize(nl); L.w_gate_up.resize(nl); L.w_down.resize(nl);
+    L.p_wqkv.resize(nl); L.p_wo.resize(nl); L.p_w_gate_up.resize(nl); L.p_w_down.resize(nl);
+    for (size_t l = 0; l < nl; ++l) {
+        L.attn_norm[l] = take(H * 2);
+        L.wqkv[l] = take(R * H * 2);
+        L.bqkv[l] = c->qkv_bias ? take(R * 2) : 0;
+        L.wo[l] = take(H * qd * 2);
+        L.mlp_norm[l] = take(H * 2);
+        L.w_gate_up[l] = take(2 * I * H * 2);
+        L.w_down[l] = take(H * I * 2);
+        L.p_wqkv[l] = take(R * H * 2);
+        L.p_wo[l] = take(H * qd * 2);
+        L.p_w_gate_up[l] = take(2 * I * H * 2);
+        L.p_w_down[l] = take(H * I * 2);
+    }
+    L.rope_cos = take(Tm * (d / 2) * 4);
+    L.rope_sin = take(Tm * (d / 2) * 4);
+    L.kcache = take(nl * kvd * Tm * 2);
+    L.vcache = take(nl * kvd * Tm * 2);
+    L.x = take(H * 4);
+    L.q = take(qd * 4);
+    L.o = take(qd * 4);
+    L.h = take(I * 4);
+    L.part = take((size_t)c->n_q_heads * ATTN_SPLITS * (d + 2) * 4);
+    L.counters = take(c->n_kv_heads * 4);
+    L.logits = take(V * 4);
+    L.hidden = take(H * 4);
+    L.part_val = take(MAX_PARTIALS * 4);
+    L.part_idx = take(MAX_PARTIALS * 4);
+    L.ints = take(64);
+    const size_t ctx_pad = (Tm + 63) / 64 * 64;
+    L.X = take(Tm * H * 4);
+    L.Ahi = take(Tm * H * 2);
+    L.Alo = take(Tm * H * 2);
+    L.QKV = take(Tm * R * 4);
+    L.Qs = take(3 * Tm * qd * 2);
+    L.Ohi = take(Tm * qd * 2);
+    L.Olo = take(Tm * qd * 2);
+    L.Hhi = take(Tm * I * 2);
+    L.Hlo = take(Tm * I * 2);
+    L.Vt = take(kvd * ctx_pad * 2);
+    L.tok = take(Tm * 4);
+    L.total = off;
+}
+
+}  // namespace
+
+struct edgefm_model {
+    edgefm_config cfg;
+    Dims D;
+    Geo G;
+    Layout L;
+    char *arena;
+    hipStream_t stream;
+    hipStream_t cap_stream;
+    hipGraph_t graph;
+    hipGraphExec_t graph_exec;
+    bool graph_ready, use_graph;
+    uint32_t kv_len;       // host mirror of the device-side position counter
+    bool have_prev_token;  // a greedy token from the previous call is waiting in device memory
+    int last_hip;
+    // pinned staging
+    int32_t *pin_tok;  // [max_seq_len]
+    float *pin_logits; // [vocab]
+    int32_t *pin_next; // [1]
+    int n_part;        // lm_head partial count
+    std::vector<LayerW> LW;
+    struct PrefillW { const uint16_t *wqkv, *wo, *w_gate_up, *w_down; };
+    std::vector<PrefillW> PW;
+
+    template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(arena + off); }
+    int *d_pos() const { return at<int>(L.ints); }
+    int *d_token() const { return at<int>(L.ints) + 1; }
+    int *d_next() const { return at<int>(L.ints) + 2; }
+    uint16_t *kc(int l) const { return at<uint16_t>(L.kcache) + (size_t)l * D.kvd() * D.max_seq; }
+    uint16_t *vc(int l) const { return at<uint16_t>(L.vcache) + (size_t)l * D.kvd() * D.max_seq; }
+    const uint16_t *lm() const { return at<uint16_t>(L.lm_head); }
+};
+
+#define HIPCHK(m, call)                      \
+    do {                                     \
+        hipError_t e_ = (call);              \
+        if (e_ != hipSuccess) {              \
+            (m)->last_hip = (int)e_;         \
+            return EDGEFM_ERR_HIP;           \
+        }                                    \
+    } while (0)
+
+namespace {
+
+// The decode step as a fixed kernel sequence (Section 3.10: one fixed graph per step; the hot-spot
+// order of Section 3.4: QKV+RoPE+KV write, decode attention, OProj, GateUp, DownProj, sampling).
+void enqueue_decode(edgefm_model *m, hipStream_t st) {
+    const Dims &D = m->D;
+    float *x = m->at<float>(m->L.x), *q = m->at<float>(m->L.q), *o = m->at<float>(m->L.o),
+          *h = m->at<float>(m->L.h);
+    launch_embed(D, m->at<uint16_t>(m->L.embed), m->d_token(), x, st);
+    for (int l = 0; l < D.L; ++l) {
+        const LayerW &W = m->LW[l];
+        launch_qkv(D, m->G, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
+                   m->vc(l), st);
+        launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
+                           m->at<uint32_t>(m->L.counters), o, st);
+        launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st);
+        launch_gateup(D, m->G, W, x, h, st);
+        launch_gemv_resid(D, m->G, W.w_down, D.I, h, x, st);
+    }
+    launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), x, m->at<float>(m->L.logits),
+                  m->at<float>(m->L.hidden), m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), &m->n_part, st);
+    launch_finish(m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), m->n_part, m->d_next(), m->d_token(),
+                  m->d_pos(), 1, st);
+}
+
+int build_graph(edgefm_model *m) {
+    HIPCHK(m, hipStreamBeginCapture(m->cap_stream, hipStreamCaptureModeThreadLocal));
+    enqueue_decode(m, m->cap_stream);
+    hipError_t e = hipStreamEndCapture(m->cap_stream, &m->graph);
+    if (e != hipSuccess) {
+        m->last_hip = (int)e;
+        return EDGEFM_ERR_HIP;
+    }
+    HIPCHK(m, hipGraphInstantiate(&m->graph_exec, m->graph, nullptr, nullptr, 0));
+    m->graph_ready = true;
+    return EDGEFM_OK;
+}
+
+int fetch_outputs(edgefm_model *m, float *logits_host, int32_t *next_host) {
+    if (logits_host)
+        HIPCHK(m, hipMemcpyAsync(m->pin_logits, m->at<float>(m->L.logits), (size_t)m->D.V * 4, hipMemcpyDeviceToHost,
+                                 m->stream));
+    if (next_host) HIPCHK(m, hipMemcpyAsync(m->pin_next, m->d_next(), 4, hipMemcpyDeviceToHost, m->stream));
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    HIPCHK(m, hipGetLastError());
+    if (logits_host) memcpy(logits_host, m->pin_logits, (size_t)m->D.V * 4);
+    if (next_host) *next_host = *m->pin_next;
+    return EDGEFM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int edgefm_query_sizes(const edgefm_config *cfg, size_t *arena_bytes) {
+    if (!valid_config(cfg) || !arena_bytes) return EDGEFM_ERR_INVALID_ARG;
+    Layout L;
+    make_layout(cfg, L);
+    *arena_bytes = L.total;
+    return EDGEFM_OK;
+}
+
+int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *arena_dev, size_t arena_bytes,
+                      void *hip_stream, edgefm_model **out) {
+    if (!out) return EDGEFM_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!valid_config(cfg) || !w || !arena_dev) return EDGEFM_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(arena_dev) % ALIGN) return EDGEFM_ERR_INVALID_ARG;
+    if (!w->embed || !w->final_norm || (!cfg->tie_embeddings && !w->lm_head) || !w->attn_norm || !w->wqkv ||
+        !w->wo || !w->mlp_norm || !w->w_gate_up || !w->w_down || (cfg->qkv_bias && !w->bqkv))
+        return EDGEFM_ERR_INVALID_ARG;
+    for (uint32_t l = 0; l < cfg->n_layers; ++l)
+        if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->mlp_norm[l] || !w->w_gate_up[l] || !w->w_down[l] ||
+            (cfg->qkv_bias && !w->bqkv[l]))
+            return EDGEFM_ERR_INVALID_ARG;
+
+    edgefm_model *m = new (std::nothrow) edgefm_model();
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    m->cfg = *cfg;
+    make_layout(cfg, m->L);
+    if (arena_bytes < m->L.total) {
+        delete m;
+        return EDGEFM_ERR_ARENA_TOO_SMALL;
+    }
+    m->arena = static_cast<char *>(arena_dev);
+    m->stream = static_cast<hipStream_t>(hip_stream);
+    m->cap_stream = nullptr;
+    m->graph = nullptr;
+    m->graph_exec = nullptr;
+    m->graph_ready = false;
+    const char *ng = getenv("EDGEFM_NO_GRAPH");
+    m->use_graph = !(ng && ng[0] == '1');
+    m->kv_len = 0;
+    m->have_prev_token = false;
+    m->last_hip = 0;
+    m->pin_tok = nullptr;
+    m->pin_logits = nullptr;
+    m->pin_next = nullptr;
+    m->n_part = 0;
+    Dims &D = m->D;
+    D.L = cfg->n_layers; D.H = cfg->hidden; D.nq = cfg->n_q_heads; D.nkv = cfg->n_kv_heads; D.d = cfg->head_dim;
+    D.I = cfg->intermediate; D.V = cfg->vocab; D.max_seq = cfg->max_seq_len;
+    D.wdt = cfg->weight_dtype; D.kvdt = cfg->kv_dtype; D.qkv_bias = cfg->qkv_bias; D.eps = cfg->rms_eps;
+
+#define LOADCHK(call)                         \
+    do {                                      \
+        hipError_t e_ = (call);               \
+        if (e_ != hipSuccess) {               \
+            int code_ = (int)e_;              \
+            edgefm_model_free(m);             \
+            (void)code_;                      \
+            return EDGEFM_ERR_HIP;            \
+        }                                     \
+    } while (0)
+
+    int dev = 0, n_cu = 0, max_lds = 0;
+    LOADCHK(hipGetDevice(&dev));
+    LOADCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    LOADCHK(hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    m->G.n_cu = n_cu > 0 ? n_cu : 256;
+    m->G.attn_splits = ATTN_SPLITS;
+    {
+        size_t need = (size_t)(D.H > D.I ? D.H : D.I) * 4;
+        if ((size_t)D.qd() * 4 > need) need = (size_t)D.qd() * 4;
+        if (need + 1024 > (size_t)max_lds || lmhead_blocks(D, m->G) > MAX_PARTIALS) {
+            edgefm_model_free(m);
+            return EDGEFM_ERR_INVALID_ARG;
+        }
+    }
+    LOADCHK(kernels_prepare(D));
+    LOADCHK(hipStreamCreateWithFlags(&m->cap_stream, hipStreamNonBlocking));
+    LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_tok), (size_t)D.max_seq * 4, hipHostMallocDefault));
+    LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_logits), (size_t)D.V * 4, hipHostMallocDefault));
+    LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_next), 64, hipHostMallocDefault));
+
+    // copy the canonical tensors into the arena
+    const size_t H = D.H, I = D.I, V = D.V, qd = D.qd(), R = D.R();
+    auto cp = [&](size_t off, const void *src, size_t bytes) {
+        return hipMemcpyAsync(m->arena + off, src, bytes, hipMemcpyDeviceToDevice, m->stream);
+    };
+    LOADCHK(cp(m->L.embed, w->embed, V * H * 2));
+    if (!cfg->tie_embeddings) LOADCHK(cp(m->L.lm_head, w->lm_head, V * H * 2));
+    LOADCHK(cp(m->L.final_norm, w->final_norm, H * 2));
+    m->LW.resize(D.L);
+    m->PW.resize(D.L);
+    for (int l = 0; l < D.L; ++l) {
+        LOADCHK(cp(m->L.attn_norm[l], w->attn_norm[l], H * 2));
+        LOADCHK(cp(m->L.wqkv[l], w->wqkv[l], R * H * 2));
+        if (cfg->qkv_bias) LOADCHK(cp(m->L.bqkv[l], w->bqkv[l], R * 2));
+        LOADCHK(cp(m->L.wo[l], w->wo[l], H * qd * 2));
+        LOADCHK(cp(m->L.mlp_norm[l], w->mlp_norm[l], H * 2));
+        LOADCHK(cp(m->L.w_gate_up[l], w->w_gate_up[l], 2 * I * H * 2));
+        LOADCHK(cp(m->L.w_down[l], w->w_down[l], H * I * 2));
+        LayerW &lw = m->LW[l];
+        lw.attn_norm = m->at<uint16_t>(m->L.attn_norm[l]);
+        lw.wqkv = m->at<uint16_t>(m->L.wqkv[l]);
+        lw.bqkv = cfg->qkv_bias ? m->at<uint16_t>(m->L.bqkv[l]) : nullptr;
+        lw.wo = m->at<uint16_t>(m->L.wo[l]);
+        lw.mlp_norm = m->at<uint16_t>(m->L.mlp_norm[l]);
+        lw.w_gate_up = m->at<uint16_t>(m->L.w_gate_up[l]);
+        lw.w_down = m->at<uint16_t>(m->L.w_down[l]);
+        // f16 copies for the prefill GEMMs, converted from the arena copies (same stream: ordered)
+        launch_convert_w16(D, lw.wqkv, m->at<uint16_t>(m->L.p_wqkv[l]), R * H, m->stream);
+        launch_convert_w16(D, lw.wo, m->at<uint16_t>(m->L.p_wo[l]), H * qd, m->stream);
+        launch_convert_w16(D, lw.w_gate_up, m->at<uint16_t>(m->L.p_w_gate_up[l]), 2 * I * H, m->stream);
+        launch_convert_w16(D, lw.w_down, m->at<uint16_t>(m->L.p_w_down[l]), H * I, m->stream);
+        m->PW[l].wqkv = m->at<uint16_t>(m->L.p_wqkv[l]);
+        m->PW[l].wo = m->at<uint16_t>(m->L.p_wo[l]);
+        m->PW[l].w_gate_up = m->at<uint16_t>(m->L.p_w_gate_up[l]);
+        m->PW[l].w_down = m->at<uint16_t>(m->L.p_w_down[l]);
+    }
+    // RoPE table: angle = pos * theta^(-2i/d), evaluated in double, stored fp32
+    {
+        const int half = D.d / 2;
+        std::vector<float> cs((size_t)D.max_seq * half), sn((size_t)D.max_seq * half);
+        std::vector<double> inv(half);
+        for (int i = 0; i < half; ++i) inv[i] = pow((double)cfg->rope_theta, -2.0 * i / (double)D.d);
+        for (int p = 0; p < D.max_seq; ++p)
+            for (int i = 0; i < half; ++i) {
+                const double a = (double)p * inv[i];
+                cs[(size_t)p * half + i] = (float)cos(a);
+                sn[(size_t)p * half + i] = (float)sin(a);
+            }
+        LOADCHK(hipMemcpy(m->arena + m->L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
+        LOADCHK(hipMemcpy(m->arena + m->L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice));
+    }
+    // attention arrival counters and the step parameters start at zero (fill kernel, not a memset node)
+    launch_fill_u16(m->at<uint16_t>(m->L.counters), (size_t)D.nkv * 2, 0, m->stream);
+    launch_fill_u16(m->at<uint16_t>(m->L.ints), 32, 0, m->stream);
+    LOADCHK(hipStreamSynchronize(m->stream));
+    LOADCHK(hipGetLastError());
+#undef LOADCHK
+    *out = m;
+    return EDGEFM_OK;
+}
+
+void edgefm_model_free(edgefm_model *m) {
+    if (!m) return;
+    if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
+    if (m->graph) (void)hipGraphDestroy(m->graph);
+    if (m->cap_stream) (void)hipStreamDestroy(m->cap_stream);
+    if (m->pin_tok) (void)hipHostFree(m->pin_tok);
+    if (m->pin_logits) (void)hipHostFree(m->pin_logits);
+    if (m->pin_next) (void)hipHostFree(m->pin_next);
+    delete m;
+}
+
+int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, const void *embeds_dev,
+                   uint32_t n_embeds, float *logits_host, int32_t *next_host) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    const uint64_t n64 = (uint64_t)n_tokens + n_embeds;
+    if (n64 == 0 || (n_tokens && !tok_host) || (n_embeds && !embeds_dev)) return EDGEFM_ERR_INVALID_ARG;
+    if ((uint64_t)m->kv_len + n64 > m->cfg.max_seq_len) return EDGEFM_ERR_CONTEXT_OVERFLOW;
+    for (uint32_t t = 0; t < n_tokens; ++t)
+        if (tok_host[t] < 0 || (uint32_t)tok_host[t] >= m->cfg.vocab) return EDGEFM_ERR_BAD_TOKEN;
+    const Dims &D = m->D;
+    const int T = (int)n64, p0 = (int)m->kv_len, ctx = p0 + T, ctx_pad = (ctx + 63) / 64 * 64;
+    hipStream_t st = m->stream;
+    int *tok = m->at<int>(m->L.tok);
+    if (n_tokens) {
+        // the staging buffer is reused by the next call: the stream is synchronised before returning
+        memcpy(m->pin_tok, tok_host, (size_t)n_tokens * 4);
+        HIPCHK(m, hipMemcpyAsync(tok, m->pin_tok, (size_t)n_tokens * 4, hipMemcpyHostToDevice, st));
+    }
+    float *X = m->at<float>(m->L.X), *QKV = m->at<float>(m->L.QKV);
+    uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo), *Qs = m->at<uint16_t>(m->L.Qs),
+             *Ohi = m->at<uint16_t>(m->L.Ohi), *Olo = m->at<uint16_t>(m->L.Olo), *Hhi = m->at<uint16_t>(m->L.Hhi),
+             *Hlo = m->at<uint16_t>(m->L.Hlo), *Vt = m->at<uint16_t>(m->L.Vt);
+    const size_t q_stride = (size_t)D.max_seq * D.qd();
+    const float *rc = m->at<float>(m->L.rope_cos), *rs = m->at<float>(m->L.rope_sin);
+    launch_embed_rows(D, m->at<uint16_t>(m->L.embed), static_cast<const uint16_t *>(embeds_dev), (int)n_embeds, tok,
+                      (int)n_tokens, X, st);
+    for (int l = 0; l < D.L; ++l) {
+        const LayerW &W = m->LW[l];
+        const edgefm_model::PrefillW &P = m->PW[l];
+        launch_rmsnorm_rows(D, X, W.attn_norm, T, Ahi, Alo, st);
+        launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, D.qkv_bias ? W.bqkv : nullptr, QKV, nullptr,
+                    nullptr, st);
+        launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, m->kc(l), m->vc(l), st);
+        launch_transpose_v(D, m->vc(l), ctx, ctx_pad, Vt, st);
+        launch_flash_attn(D, Qs, q_stride, m->kc(l), Vt, ctx_pad, T, p0, Ohi, Olo, st);
+        launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, st);
+        launch_rmsnorm_rows(D, X, W.mlp_norm, T, Ahi, Alo, st);
+        launch_gemm(D, EPI_SWIGLU, Ahi, Alo, P.w_gate_up, T, D.I, D.H, nullptr, nullptr, Hhi, Hlo, st);
+        launch_gemm(D, EPI_RESID, Hhi, Hlo, P.w_down, T, D.H, D.I, nullptr, X, nullptr, nullptr, st);
+    }
+    // only the last position needs logits: final norm + lm_head as a GEMV on that row
+    launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), X + (size_t)(T - 1) * D.H,
+                  m->at<float>(m->L.logits), m->at<float>(m->L.hidden), m->at<float>(m->L.part_val),
+                  m->at<int>(m->L.part_idx), &m->n_part, st);
+    launch_finish(m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), m->n_part, m->d_next(), m->d_token(),
+                  m->d_pos(), 0, st);
+    launch_set_int(m->d_pos(), ctx, st);
+    HIPCHK(m, hipGetLastError());
+    m->kv_len = (uint32_t)ctx;
+    m->have_prev_token = true;
+    return fetch_outputs(m, logits_host, next_host);
+}
+
+int edgefm_decode_step(edgefm_model *m, int32_t token, float *logits_host, int32_t *next_host) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    if (token < -1 || (token >= 0 && (uint32_t)token >= m->cfg.vocab)) return EDGEFM_ERR_BAD_TOKEN;
+    if (token == -1 && !m->have_prev_token) return EDGEFM_ERR_STATE;
+    if (m->kv_len + 1 > m->cfg.max_seq_len) return EDGEFM_ERR_CONTEXT_OVERFLOW;
+    if (m->use_graph && !m->graph_ready) {
+        int rc = build_graph(m);
+        if (rc != EDGEFM_OK) return rc;
+    }
+    if (token >= 0) launch_set_int(m->d_token(), token, m->stream);
+    if (m->use_graph) {
+        HIPCHK(m, hipGraphLaunch(m->graph_exec, m->stream));
+    } else {
+        enqueue_decode(m, m->stream);
+        HIPCHK(m, hipGetLastError());
+    }
+    m->kv_len += 1;
+    m->have_prev_token = true;
+    if (!logits_host && !next_host) return EDGEFM_OK;
+    return fetch_outputs(m, logits_host, next_host);
+}
+
+int edgefm_kv_reset(edgefm_model *m, uint32_t keep_len) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    if (keep_len > m->kv_len) return EDGEFM_ERR_STATE;
+    launch_set_int(m->d_pos(), (int)keep_len, m->stream);
+    HIPCHK(m, hipGetLastError());
+    m->kv_len = keep_len;
+    m->have_prev_token = false;
+    return EDGEFM_OK;
+}
+
+uint32_t edgefm_kv_len(const edgefm_model *m) { return m ? m->kv_len : 0; }
+
+int edgefm_last_hip_error(const edgefm_model *m) { return m ? m->last_hip : 0; }
+
+const char *edgefm_strerror(int status) {
+    switch (status) {
+        case EDGEFM_OK: return "ok";
+        case EDGEFM_ERR_INVALID_ARG: return "invalid argument or unsupported configuration";
+        case EDGEFM_ERR_ARENA_TOO_SMALL: return "arena too small";
+        case EDGEFM_ERR_CONTEXT_OVERFLOW: return "context overflow (kv_len + new positions > max_seq_len)";
+        case EDGEFM_ERR_BAD_TOKEN: return "token id out of range";
+        case EDGEFM_ERR_STATE: return "call not valid in the current state";
+        case EDGEFM_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int edgefm_debug_kv_read(edgefm_model *m, uint32_t layer, uint32_t pos, void *k_host, void *v_host) {
+    if (!m || !k_host || !v_host || layer >= m->cfg.n_layers || pos >= m->cfg.max_seq_len)
+        return EDGEFM_ERR_INVALID_ARG;
+    const Dims &D = m->D;
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    for (int h = 0; h < D.nkv; ++h) {
+        const size_t off = ((size_t)h * D.max_seq + pos) * D.d;
+        HIPCHK(m, hipMemcpy(static_cast<uint16_t *>(k_host) + (size_t)h * D.d, m->kc(layer) + off, (size_t)D.d * 2,
+                            hipMemcpyDeviceToHost));
+        HIPCHK(m, hipMemcpy(static_cast<uint16_t *>(v_host) + (size_t)h * D.d, m->vc(layer) + off, (size_t)D.d * 2,
+                            hipMemcpyDeviceToHost));
+    }
+    return EDGEFM_OK;
+}
+
+int edgefm_debug_kv_write(edgefm_model *m, uint32_t layer, uint32_t n_pos, const void *k_host, const void *v_host) {
+    if (!m || !k_host || !v_host || layer >= m->cfg.n_layers || n_pos > m->cfg.max_seq_len)
+        return EDGEFM_ERR_INVALID_ARG;
+    const Dims &D = m->D;
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    // host rows are [pos][head][d]; the cache is [head][pos][d]
+    const size_t src_pitch = (size_t)D.kvd() * 2, row = (size_t)D.d * 2;
+    for (int h = 0; h < D.nkv; ++h) {
+        HIPCHK(m, hipMemcpy2D(m->kc(layer) + (size_t)h * D.max_seq * D.d, row,
+                              static_cast<const char *>(k_host) + (size_t)h * row, src_pitch, row, n_pos,
+                              hipMemcpyHostToDevice));
+        HIPCHK(m, hipMemcpy2D(m->vc(layer) + (size_t)h * D.max_seq * D.d, row,
+                              static_cast<const char *>(v_host) + (size_t)h * row, src_pitch, row, n_pos,
+                              hipMemcpyHostToDevice));
+    }
+    return EDGEFM_OK;
+}
+
+int edgefm_debug_kv_fill(edgefm_model *m, uint16_t pattern) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    const size_t n = (size_t)m->D.L * m->D.kvd() * m->D.max_seq;
+    launch_fill_u16(m->at<uint16_t>(m->L.kcache), n, pattern, m->stream);
+    launch_fill_u16(m->at<uint16_t>(m->L.vcache), n, pattern, m->stream);
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    HIPCHK(m, hipGetLastError());
+    return EDGEFM_OK;
+}
+
+int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n) {
+    if (!m || n > m->cfg.max_seq_len) return EDGEFM_ERR_INVALID_ARG;
+    launch_set_int(m->d_pos(), (int)n, m->stream);
+    HIPCHK(m, hipGetLastError());
+    m->kv_len = n;
+    m->have_prev_token = false;
+    return EDGEFM_OK;
+}
+
+int edgefm_debug_last_hidden(edgefm_model *m, float *hidden_host) {
+    if (!m || !hidden_host) return EDGEFM_ERR_INVALID_ARG;
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    HIPCHK(m, hipMemcpy(hidden_host, m->at<float>(m->L.hidden), (size_t)m->D.H * 4, hipMemcpyDeviceToHost));
+    return EDGEFM_OK;
+}
+
+int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) {
+    if (!m || op < 0 || op > EDGEFM_OP_LMHEAD || layer >= (int)m->cfg.n_layers) return EDGEFM_ERR_INVALID_ARG;
+    if (m->kv_len < 1) return EDGEFM_ERR_STATE;
+    const Dims &D = m->D;
+    hipStream_t st = m->stream;
+    float *x = m->at<float>(m->L.x), *q = m->at<float>(m->L.q), *o = m->at<float>(m->L.o),
+          *h = m->at<float>(m->L.h);
+    // the position used by QKV / attention is the last valid one, so nothing outside the context is touched
+    launch_set_int(m->d_pos(), (int)m->kv_len - 1, st);
+    for (uint32_t r = 0; r < repeat; ++r) {
+        const int l = layer >= 0 ? layer : (int)(r % (uint32_t)D.L);
+        const LayerW &W = m->LW[l];
+        switch (op) {
+            case EDGEFM_OP_QKV:
+                launch_qkv(D, m->G, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q,
+                           m->kc(l), m->vc(l), st);
+                break;
+            case EDGEFM_OP_ATTN:
+                launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
+                                   m->at<uint32_t>(m->L.counters), o, st);
+                break;
+            case EDGEFM_OP_OPROJ: launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st); break;
+            case EDGEFM_OP_GATEUP: launch_gateup(D, m->G, W, x, h, st); break;
+            case EDGEFM_OP_DOWN: launch_gemv_resid(D, m->G, W.w_down, D.I, h, x, st); break;
+            case EDGEFM_OP_LMHEAD:
+                launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), x, m->at<float>(m->L.logits),
+                              m->at<float>(m->L.hidden), m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx),
+                              &m->n_part, st);
+                break;
+        }
+    }
+    launch_set_int(m->d_pos(), (int)m->kv_len, st);
+    HIPCHK(m, hipGetLastError());
+    return EDGEFM_OK;
+}
+
+}  // extern "C"

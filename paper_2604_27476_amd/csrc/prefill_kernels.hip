@@ -1,0 +1,576 @@
+// Prefill kernels (m = T; Eq. 3 of Section 3.5): the four projections per layer are dense GEMMs on the
+// 16-bit matrix cores (v_mfma_f32_32x32x16), attention is a causal GQA flash-attention on the same
+// instruction.  The residual stream, normalisation, RoPE, softmax and all accumulators stay fp32.
+//
+// Operand precision.  The KV cache is rounded to 16 bit, and a rounding flips whenever the value in
+// front of it moves across a tie, so an activation error of relative size e in front of the cache
+// becomes sqrt(e * ulp) behind it; through 28 layers this is amplified further.  A single 16-bit
+// rounding of the activations (e ~ 1e-3 for bf16, 1e-4 for f16) ends far outside the 2e-3 parity
+// tolerance at depth 28.  Activations are therefore fed to the matrix cores as a sum of 16-bit terms:
+//   GEMMs:      a = a_hi + a_lo in f16 (22 significant bits) against an f16 copy of the weights scaled
+//               by 2^8 (the prefill artifact theta_p of Section 3.5; exact for every bf16/f16 weight of
+//               magnitude >= 2^-25), two MFMAs per product;
+//   attention:  q and p as three bf16 terms (24 bits) against the bf16 cache, or two f16 terms against an
+//               f16 cache: the cache operands are used exactly as stored.
+#include "common.h"
+#include "kernels.h"
+
+namespace efm {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// D[m][n] += sum_k A[m][k] B[k][n], 32x32 output tile, 16-deep.  Lane l supplies A[m = l%32][8*(l/32)+j]
+// and B[8*(l/32)+j][n = l%32] (j = 0..7); it receives D[8*(i/4) + 4*(l/32) + i%4][l%32] in slot i.
+template <int DT> __device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, const f32x16 &c) {
+    if constexpr (DT == DT_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                      0, 0);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void k_embed_rows(const uint16_t *__restrict__ E, const uint16_t *__restrict__ embeds, int n_embeds,
+                             const int *__restrict__ tok, float *__restrict__ X, int H) {
+    const int t = blockIdx.x;
+    const uint16_t *row = t < n_embeds ? embeds + (size_t)t * H : E + (size_t)tok[t - n_embeds] * H;
+    float *x = X + (size_t)t * H;
+    for (int v = threadIdx.x; v < (H >> 3); v += blockDim.x) {
+        float f[8];
+        unpack8<DT>(ld16(row + 8 * v), f);
+        reinterpret_cast<float4 *>(x)[2 * v] = make_float4(f[0], f[1], f[2], f[3]);
+        reinterpret_cast<float4 *>(x)[2 * v + 1] = make_float4(f[4], f[5], f[6], f[7]);
+    }
+}
+
+// split an fp32 value into two f16 terms: hi = f16(v), lo = f16(v - hi)
+__device__ __forceinline__ void split_f16(float v, uint16_t &hi, uint16_t &lo) {
+    hi = down1<DT_F16>(v);
+    lo = down1<DT_F16>(v - up1<DT_F16>(hi));
+}
+struct HiLo {
+    uint32_t hi, lo;
+};
+// two values -> packed hi pair and packed lo pair (first value in the low half)
+__device__ __forceinline__ HiLo split2_f16(float a, float b) {
+    uint16_t ah, al, bh, bl;
+    split_f16(a, ah, al);
+    split_f16(b, bh, bl);
+    return HiLo{(uint32_t)ah | ((uint32_t)bh << 16), (uint32_t)al | ((uint32_t)bl << 16)};
+}
+
+// A_hi[t] + A_lo[t] = RMSNorm(X[t]) * gain  (f16 pair)
+template <int DT>
+__global__ void k_rmsnorm_rows(const float *__restrict__ X, const uint16_t *__restrict__ gain,
+                               uint16_t *__restrict__ Ahi, uint16_t *__restrict__ Alo, int H, float eps) {
+    __shared__ float red[32];
+    const float *x = X + (size_t)blockIdx.x * H;
+    uint16_t *ah = Ahi + (size_t)blockIdx.x * H, *al = Alo + (size_t)blockIdx.x * H;
+    const int nvec = H >> 3;
+    float ss = 0.f;
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        const float4 p = reinterpret_cast<const float4 *>(x)[2 * v], q = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+        ss += p.x * p.x + p.y * p.y + p.z * p.z + p.w * p.w + q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
+    }
+    ss = block_sum(ss, red);
+    const float rstd = 1.0f / sqrtf(ss / (float)H + eps);
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        const float4 p = reinterpret_cast<const float4 *>(x)[2 * v], q = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+        float g[8];
+        unpack8<DT>(ld16(gain + 8 * v), g);
+        const HiLo s0 = split2_f16(p.x * rstd * g[0], p.y * rstd * g[1]);
+        const HiLo s1 = split2_f16(p.z * rstd * g[2], p.w * rstd * g[3]);
+        const HiLo s2 = split2_f16(q.x * rstd * g[4], q.y * rstd * g[5]);
+        const HiLo s3 = split2_f16(q.z * rstd * g[6], q.w * rstd * g[7]);
+        const u32x4 oh = {s0.hi, s1.hi, s2.hi, s3.hi}, ol = {s0.lo, s1.lo, s2.lo, s3.lo};
+        *reinterpret_cast<u32x4 *>(ah + 8 * v) = oh;
+        *reinterpret_cast<u32x4 *>(al + 8 * v) = ol;
+    }
+}
+
+// f16 copy of a weight tensor, scaled by 2^8 (exact power of two, undone in the GEMM epilogue)
+constexpr float W16_SCALE = 256.0f;
+template <int DT>
+__global__ void k_convert_w16(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, size_t nvec) {
+    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (size_t)gridDim.x * blockDim.x) {
+        float f[8];
+        unpack8<DT>(ld16(src + 8 * v), f);
+        u32x4 o;
+        o.x = down2<DT_F16>(f[0] * W16_SCALE, f[1] * W16_SCALE);
+        o.y = down2<DT_F16>(f[2] * W16_SCALE, f[3] * W16_SCALE);
+        o.z = down2<DT_F16>(f[4] * W16_SCALE, f[5] * W16_SCALE);
+        o.w = down2<DT_F16>(f[6] * W16_SCALE, f[7] * W16_SCALE);
+        *reinterpret_cast<u32x4 *>(dst + 8 * v) = o;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// GEMM  C[T,N] = (A_hi + A_lo)[T,K] W16[N,K]^T / 2^8, every operand K-contiguous f16, so each MFMA operand
+// fragment is one 16-byte vector.  Workgroup tile 128 x 128 x 64, four waves in 2 x 2, each wave
+// 64 x 64 = 2 x 2 MFMA tiles; two MFMAs (hi, lo) per tile and k-step share the weight fragment.  Tiles
+// are staged through LDS (row stride 72 elements: conflict-free 128-bit reads) with the next tile's
+// global loads in flight during the MFMAs.
+// ------------------------------------------------------------------------------------------------
+constexpr int BM = 128, BN = 128, BK = 64, LDK = 72;
+
+template <int BDT, int EPI>
+__global__ void __launch_bounds__(256)
+k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
+       int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
+       uint16_t *__restrict__ olo) {
+    __shared__ __attribute__((aligned(16))) uint16_t sAh[BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t sAl[BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * BM;
+    const int nb = blockIdx.x;  // n-tile index
+
+    // global source row of LDS row r of the B tile, or -1 if outside the matrix
+    auto brow = [&](int r) -> int {
+        if constexpr (EPI == EPI_SWIGLU) {
+            const int j = nb * 64 + (r >> 6) * 32 + (r & 31);  // gate/up column
+            return j < N ? ((r >> 5) & 1) * N + j : -1;        // N = I; gate rows [0,I), up rows [I,2I)
+        } else {
+            const int n = nb * BN + r;
+            return n < N ? n : -1;
+        }
+    };
+
+    // each thread moves 4 vectors of A_hi, A_lo and W per k-tile: vector id = tid + 256*i -> (row, kvec)
+    size_t oa[4], ob[4];
+    bool va[4], vb[4];
+    int so[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int vid = tid + 256 * i, r = vid >> 3, kv = vid & 7;
+        const int m = m0 + r;
+        va[i] = m < T;
+        oa[i] = (size_t)(va[i] ? m : 0) * K + kv * 8;
+        const int br = brow(r);
+        vb[i] = br >= 0;
+        ob[i] = (size_t)(vb[i] ? br : 0) * K + kv * 8;
+        so[i] = r * LDK + kv * 8;
+    }
+    u32x4 rah[4], ral[4], rb[4];
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool kin = k0 + ((tid + 256 * i) & 7) * 8 < K;
+            rah[i] = (va[i] && kin) ? ld16(Ahi + oa[i] + k0) : zero;
+            ral[i] = (va[i] && kin) ? ld16(Alo + oa[i] + k0) : zero;
+            rb[i] = (vb[i] && kin) ? ld16(W + ob[i] + k0) : zero;
+        }
+    };
+    auto sstore = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<u32x4 *>(sAh + so[i]) = rah[i];
+            *reinterpret_cast<u32x4 *>(sAl + so[i]) = ral[i];
+            *reinterpret_cast<u32x4 *>(sB + so[i]) = rb[i];
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int nk = (K + BK - 1) / BK;
+    gload(0);
+    sstore();
+    __syncthreads();
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) gload((kt + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            u32x4 fah[2], fal[2], fb[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int ao = (wm * 64 + t * 32 + fr) * LDK + ks * 16 + fk;
+                fah[t] = *reinterpret_cast<const u32x4 *>(sAh + ao);
+                fal[t] = *reinterpret_cast<const u32x4 *>(sAl + ao);
+                fb[t] = *reinterpret_cast<const u32x4 *>(sB + (wn * 64 + t * 32 + fr) * LDK + ks * 16 + fk);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    acc[a][b] = mfma32<DT_F16>(fah[a], fb[b], acc[a][b]);
+                    acc[a][b] = mfma32<DT_F16>(fal[a], fb[b], acc[a][b]);
+                }
+        }
+        __syncthreads();
+        if (kt + 1 < nk) {
+            sstore();
+            __syncthreads();
+        }
+    }
+
+    // epilogue: slot i of tile (a, b) is row wm*64 + a*32 + 8*(i/4) + 4*(lane/32) + i%4, column lane%32
+    const int hf = lane >> 5;
+    constexpr float UNSCALE = 1.0f / W16_SCALE;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wm * 64 + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+            if (m >= T) continue;
+            if constexpr (EPI == EPI_SWIGLU) {
+                const int j = nb * 64 + wn * 32 + fr;
+                if (j < N) {
+                    const float g = acc[a][0][i] * UNSCALE, u = acc[a][1][i] * UNSCALE;
+                    uint16_t h, l;
+                    split_f16(g / (1.0f + expf(-g)) * u, h, l);
+                    ohi[(size_t)m * N + j] = h;
+                    olo[(size_t)m * N + j] = l;
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const int n = nb * BN + wn * 64 + b * 32 + fr;
+                    if (n < N) {
+                        const float c = acc[a][b][i] * UNSCALE;
+                        if constexpr (EPI == EPI_RESID) outf[(size_t)m * N + n] += c;
+                        else outf[(size_t)m * N + n] = c + (bias ? up1<BDT>(bias[n]) : 0.f);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// RoPE (rotate-half pairing, Appendix B.3) + KV-cache write for T new positions starting at p0.
+// One thread per (t, head, i < d/2).  The rotated query is stored as NS terms of the cache dtype
+// (q = q_1 + ... + q_NS), the MFMA partner format of the cached K.
+// ------------------------------------------------------------------------------------------------
+template <int KDT> struct SplitN { static constexpr int NS = (KDT == DT_BF16) ? 3 : 2; };
+
+template <int KDT, int NS>
+__device__ __forceinline__ void split_terms(float v, uint16_t (&t)[NS]) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        t[s] = down1<KDT>(v);
+        v -= up1<KDT>(t[s]);
+    }
+}
+
+template <int KDT>
+__global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const float *__restrict__ rope_cos,
+                          const float *__restrict__ rope_sin, uint16_t *__restrict__ Qs, size_t q_stride,
+                          uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, int nq, int nkv, int d, int max_seq) {
+    constexpr int NS = SplitN<KDT>::NS;
+    const int half = d >> 1, per_t = (nq + 2 * nkv) * half;
+    const size_t total = (size_t)T * per_t;
+    const int R = (nq + 2 * nkv) * d;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int t = (int)(idx / per_t), u = (int)(idx - (size_t)t * per_t);
+        const int hh = u / half, i = u - hh * half;
+        const float *row = QKV + (size_t)t * R + hh * d;
+        float v0 = row[i], v1 = row[i + half];
+        const int pos = p0 + t;
+        if (hh < nq + nkv) {
+            const float c = rope_cos[(size_t)pos * half + i], s = rope_sin[(size_t)pos * half + i];
+            const float y0 = v0 * c - v1 * s, y1 = v1 * c + v0 * s;
+            v0 = y0;
+            v1 = y1;
+        }
+        if (hh < nq) {
+            uint16_t a[NS], b[NS];
+            split_terms<KDT, NS>(v0, a);
+            split_terms<KDT, NS>(v1, b);
+            uint16_t *dst = Qs + (size_t)t * nq * d + hh * d;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                dst[s * q_stride + i] = a[s];
+                dst[s * q_stride + i + half] = b[s];
+            }
+        } else {
+            uint16_t *dst = hh < nq + nkv ? kc + ((size_t)(hh - nq) * max_seq + pos) * d
+                                          : vc + ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
+            dst[i] = down1<KDT>(v0);
+            dst[i + half] = down1<KDT>(v1);
+        }
+    }
+}
+
+// Vt[kvh][i][j] = V[kvh][j][i] for j < ctx, zero for ctx <= j < ctx_pad.  64 x 64 tiles through LDS.
+__global__ void __launch_bounds__(256)
+k_transpose_v(const uint16_t *__restrict__ vc, int ctx, int ctx_pad, uint16_t *__restrict__ Vt, int d, int max_seq) {
+    __shared__ uint16_t tile[64][66];
+    const int kvh = blockIdx.z, j0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
+    const uint16_t *src = vc + (size_t)kvh * max_seq * d;
+    uint16_t *dst = Vt + (size_t)kvh * d * ctx_pad;
+    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+        const int j = e >> 6, i = e & 63;
+        tile[j][i] = (j0 + j < ctx) ? src[(size_t)(j0 + j) * d + i0 + i] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+        const int i = e >> 6, j = e & 63;
+        dst[(size_t)(i0 + i) * ctx_pad + j0 + j] = tile[j][i];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Causal GQA flash attention.  Workgroup = one query head x 128 queries; wave = 32 queries.
+// Per 64-key tile:  S^T = K Q^T  (keys x queries, so a lane owns one query column and the softmax row
+// statistics need a single exchange with lane^32), online softmax in fp32, then  O^T += V^T P^T  where
+// the P^T operand is taken straight from the S^T accumulator registers: lane half h holds keys
+// {4h..4h+3, 8+4h..8+4h+3} of each 16-key group, and the V^T operand is read from LDS in that same key
+// order.  q and p enter the matrix cores as NS 16-bit terms each; K and V^T as stored.  Masked scores
+// are replaced by a finite sentinel (Appendix B.3 item 3); their probability is set to exactly zero.
+// The output is written as an f16 pair (hi, lo): the A operand of the O projection.
+// ------------------------------------------------------------------------------------------------
+template <int KDT, int D>
+__global__ void __launch_bounds__(256)
+k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *__restrict__ kc,
+             const uint16_t *__restrict__ Vt, int ctx_pad, int T, int p0, uint16_t *__restrict__ Ohi,
+             uint16_t *__restrict__ Olo, int nq, int g, int max_seq, float scale) {
+    constexpr int NS = SplitN<KDT>::NS;
+    constexpr int LK = D + 8;    // K tile row stride (elements)
+    constexpr int LV = 64 + 4;   // V^T tile row stride (elements)
+    constexpr int NKS = D / 16;  // MFMA k-steps over the head dimension
+    constexpr int NDB = D / 32;  // 32-row blocks of O^T
+    __shared__ __attribute__((aligned(16))) uint16_t sK[64 * LK];
+    __shared__ __attribute__((aligned(16))) uint16_t sV[D * LV];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 31, hf = lane >> 5;
+    const int h = blockIdx.y, kvh = h / g;
+    const int qb0 = blockIdx.x * 128;
+    const int tq = qb0 + wave * 32 + fr;  // this lane's query (index into the new block)
+    const int qd = nq * D;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    u32x4 qf[NS][NKS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            qf[s][ks] = tq < T ? ld16(Qs + s * q_stride + (size_t)tq * qd + h * D + ks * 16 + hf * 8) : zero;
+
+    f32x16 oacc[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    float mrow = -1.0e30f, lrow = 0.f;
+
+    const int last_q = min(T, qb0 + 128) - 1;    // last query of the workgroup
+    const int n_tiles = (p0 + last_q) / 64 + 1;  // key tiles 0 .. n_tiles-1 hold keys <= p0 + last_q
+    const int wave_last_key = p0 + min(T - 1, qb0 + wave * 32 + 31);
+    const uint16_t *kbase = kc + (size_t)kvh * max_seq * D;
+    const uint16_t *vbase = Vt + (size_t)kvh * D * ctx_pad;
+    const int ctx = p0 + T;
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int key0 = kt * 64;
+        __syncthreads();  // previous tile fully consumed
+        // K tile: 64 keys x D -> 64 * D/8 vectors
+        for (int vid = tid; vid < 64 * (D / 8); vid += 256) {
+            const int r = vid / (D / 8), c = vid % (D / 8);
+            const int key = key0 + r;
+            const u32x4 v = key < ctx ? ld16(kbase + (size_t)key * D + c * 8) : zero;
+            *reinterpret_cast<u32x4 *>(sK + r * LK + c * 8) = v;
+        }
+        // V^T tile: D rows x 64 keys -> D * 8 vectors (padding columns of Vt are zero)
+        for (int vid = tid; vid < D * 8; vid += 256) {
+            const int r = vid >> 3, c = vid & 7;
+            const u32x4 v = ld16(vbase + (size_t)r * ctx_pad + key0 + c * 8);
+            u32x2 *dst = reinterpret_cast<u32x2 *>(sV + r * LV + c * 8);
+            dst[0] = u32x2{v.x, v.y};
+            dst[1] = u32x2{v.z, v.w};
+        }
+        __syncthreads();
+        if (key0 > wave_last_key) continue;  // tile entirely above this wave's diagonal (wave-uniform)
+
+        // S^T = K Q^T : two 32-key blocks
+        f32x16 sacc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const u32x4 kf = *reinterpret_cast<const u32x4 *>(sK + (kb * 32 + fr) * LK + ks * 16 + hf * 8);
+#pragma unroll
+                for (int s = NS - 1; s >= 0; --s) sacc[kb] = mfma32<KDT>(kf, qf[s][ks], sacc[kb]);
+            }
+        }
+        // online softmax for this lane's query
+        const int qpos = p0 + tq;
+        float mx = -1.0e30f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+                const float sv = key <= qpos ? sacc[kb][i] * scale : -1.0e30f;
+                sacc[kb][i] = sv;
+                mx = fmaxf(mx, sv);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+        const float mnew = fmaxf(mrow, mx);
+        const float corr = expf(mrow - mnew);
+        mrow = mnew;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float sv = sacc[kb][i];
+                const float pv = sv > -0.5e30f ? expf(sv - mnew) : 0.f;
+                sacc[kb][i] = pv;
+                psum += pv;
+            }
+        lrow = lrow * corr + psum;  // per-lane partial; the two lanes of a query are added at the end
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[db][i] *= corr;
+        // O^T += V^T P^T, 16 keys per MFMA, NS terms of p
+#pragma unroll
+        for (int ks2 = 0; ks2 < 4; ++ks2) {
+            const int kb = ks2 >> 1, ib = (ks2 & 1) * 8;
+            uint16_t pt[8][NS];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) split_terms<KDT, NS>(sacc[kb][ib + j], pt[j]);
+            u32x4 pf[NS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                pf[s].x = (uint32_t)pt[0][s] | ((uint32_t)pt[1][s] << 16);
+                pf[s].y = (uint32_t)pt[2][s] | ((uint32_t)pt[3][s] << 16);
+                pf[s].z = (uint32_t)pt[4][s] | ((uint32_t)pt[5][s] << 16);
+                pf[s].w = (uint32_t)pt[6][s] | ((uint32_t)pt[7][s] << 16);
+            }
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const uint16_t *vr = sV + (db * 32 + fr) * LV + ks2 * 16 + hf * 4;
+                const u32x2 v0 = *reinterpret_cast<const u32x2 *>(vr);
+                const u32x2 v1 = *reinterpret_cast<const u32x2 *>(vr + 8);
+                const u32x4 vf = {v0.x, v0.y, v1.x, v1.y};
+#pragma unroll
+                for (int s = NS - 1; s >= 0; --s) oacc[db] = mfma32<KDT>(vf, pf[s], oacc[db]);
+            }
+        }
+    }
+    const float ltot = lrow + __shfl_xor(lrow, 32, WAVE);
+    if (tq < T) {
+        const float inv = 1.0f / ltot;
+        uint16_t *oh = Ohi + (size_t)tq * qd + h * D, *ol = Olo + (size_t)tq * qd + h * D;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int dd = db * 32 + 8 * i4 + 4 * hf;
+                const HiLo s0 = split2_f16(oacc[db][4 * i4 + 0] * inv, oacc[db][4 * i4 + 1] * inv);
+                const HiLo s1 = split2_f16(oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
+                const u32x2 vh = {s0.hi, s1.hi}, vl = {s0.lo, s1.lo};
+                *reinterpret_cast<u32x2 *>(oh + dd) = vh;
+                *reinterpret_cast<u32x2 *>(ol + dd) = vl;
+            }
+    }
+}
+
+// ================================================================================================
+// launchers
+// ================================================================================================
+void launch_embed_rows(const Dims &D, const uint16_t *embed, const uint16_t *embeds, int n_embeds, const int *tok,
+                       int n_tokens, float *X, hipStream_t st) {
+    const int T = n_embeds + n_tokens;
+    if (D.wdt == DT_BF16)
+        hipLaunchKernelGGL(k_embed_rows<DT_BF16>, dim3(T), dim3(256), 0, st, embed, embeds, n_embeds, tok, X, D.H);
+    else
+        hipLaunchKernelGGL(k_embed_rows<DT_F16>, dim3(T), dim3(256), 0, st, embed, embeds, n_embeds, tok, X, D.H);
+}
+
+void launch_rmsnorm_rows(const Dims &D, const float *X, const uint16_t *gain, int T, uint16_t *Ahi, uint16_t *Alo,
+                         hipStream_t st) {
+    if (D.wdt == DT_BF16)
+        hipLaunchKernelGGL(k_rmsnorm_rows<DT_BF16>, dim3(T), dim3(256), 0, st, X, gain, Ahi, Alo, D.H, D.eps);
+    else
+        hipLaunchKernelGGL(k_rmsnorm_rows<DT_F16>, dim3(T), dim3(256), 0, st, X, gain, Ahi, Alo, D.H, D.eps);
+}
+
+void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, size_t n, hipStream_t st) {
+    const size_t nvec = n / 8;
+    size_t blocks = (nvec + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    if (D.wdt == DT_BF16)
+        hipLaunchKernelGGL(k_convert_w16<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, nvec);
+    else
+        hipLaunchKernelGGL(k_convert_w16<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, nvec);
+}
+
+template <int BDT>
+static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, hipStream_t st) {
+    const dim3 block(256);
+    const int mt = (T + BM - 1) / BM;
+    if (epi == EPI_SWIGLU) {
+        const dim3 grid((N + 63) / 64, mt);
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_SWIGLU>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo);
+    } else if (epi == EPI_RESID) {
+        const dim3 grid((N + BN - 1) / BN, mt);
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_RESID>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo);
+    } else {
+        const dim3 grid((N + BN - 1) / BN, mt);
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo);
+    }
+}
+
+void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
+                 int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, hipStream_t st) {
+    if (D.wdt == DT_BF16) gemm_dt<DT_BF16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, st);
+    else gemm_dt<DT_F16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, st);
+}
+
+void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
+                    uint16_t *Qs, size_t q_stride, uint16_t *kc, uint16_t *vc, hipStream_t st) {
+    const size_t total = (size_t)T * (D.nq + 2 * D.nkv) * (D.d / 2);
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 65535) blocks = 65535;
+    if (D.kvdt == DT_BF16)
+        hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, T, p0, rope_cos, rope_sin,
+                           Qs, q_stride, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
+    else
+        hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, T, p0, rope_cos, rope_sin,
+                           Qs, q_stride, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
+}
+
+void launch_transpose_v(const Dims &D, const uint16_t *vc, int ctx, int ctx_pad, uint16_t *Vt, hipStream_t st) {
+    const dim3 grid(ctx_pad / 64, D.d / 64, D.nkv);
+    hipLaunchKernelGGL(k_transpose_v, grid, dim3(256), 0, st, vc, ctx, ctx_pad, Vt, D.d, D.max_seq);
+}
+
+template <int KDT>
+static void fa_d(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *kc, const uint16_t *Vt,
+                 int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st) {
+    const dim3 grid((T + 127) / 128, D.nq), block(256);
+    const float scale = 1.0f / sqrtf((float)D.d);
+    if (D.d == 128)
+        hipLaunchKernelGGL((k_flash_attn<KDT, 128>), grid, block, 0, st, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo,
+                           D.nq, D.g(), D.max_seq, scale);
+    else
+        hipLaunchKernelGGL((k_flash_attn<KDT, 64>), grid, block, 0, st, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo,
+                           D.nq, D.g(), D.max_seq, scale);
+}
+
+void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *kc, const uint16_t *Vt,
+                       int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st) {
+    if (D.kvdt == DT_BF16) fa_d<DT_BF16>(D, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo, st);
+    else fa_d<DT_F16>(D, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo, st);
+}
+
+}  // namespace efm
