@@ -147,9 +147,10 @@ static void matmul_block(const uint16_t *W, const uint16_t *bias, uint32_t dtype
             const uint16_t *w = W + (size_t)r * cols;
             for (uint32_t t = 0; t < n; ++t) acc[t] = 0;
             for (uint32_t k = 0; k < cols; ++k) {
-                real wk = (real)bits_to_double(w[k], dtype);
-                const real *a = At + (size_t)k * n;
-                for (uint32_t t = 0; t < n; ++t) acc[t] += wk * a[t];
+                const real wk = (real)bits_to_double(w[k], dtype);
+                const real *restrict a = At + (size_t)k * n;
+                real *restrict s = acc;
+                for (uint32_t t = 0; t < n; ++t) s[t] += wk * a[t]; /* n independent sums, each in k order */
             }
             real b = bias ? (real)bits_to_double(bias[r], dtype) : (real)0;
             for (uint32_t t = 0; t < n; ++t) Y[(size_t)t * rows + r] = acc[t] + b;

@@ -13,7 +13,7 @@ import os
 
 import numpy as np
 
-from .build import lib_path
+from .buildlib import lib_path
 
 EDGEFM_F16, EDGEFM_BF16 = 1, 2
 EDGEFM_OK = 0

@@ -1,0 +1,370 @@
+"""Parity of the HIP path (through the C ABI of libedgefm.so) against the CPU oracle on the same seeded
+inputs.  Bars: relative L2 <= 2e-3 on the final hidden state and on the logits; greedy token ids equal
+wherever the oracle's top-2 logit margin exceeds 5e-2 (otherwise either of the oracle's top two is
+accepted); the run is teacher-forced with the oracle's tokens so that later positions stay comparable;
+KV-cache indexing exact (sentinel outside the valid range, every row nearest to the oracle's row of the
+same position)."""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from paper_2604_27476_amd import binding
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 2e-3
+MARGIN = 5e-2
+SENTINEL = 0x7FFF  # a NaN pattern in both binary16 and bfloat16
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def check_token(g_next, o_logits, where):
+    order = np.argsort(-o_logits, kind="stable")[:2]
+    margin = o_logits[order[0]] - o_logits[order[1]]
+    if margin > MARGIN:
+        assert g_next == order[0], f"{where}: token {g_next} != oracle {order[0]} at margin {margin:.3f}"
+        return True
+    assert g_next in order, f"{where}: token {g_next} not in the oracle's top two {order}"
+    return False
+
+
+class Pair:
+    """An oracle model and a GPU model built from the same weights."""
+
+    def __init__(self, shape, n_layers=None, max_seq_len=None, seed=synth.SEED_WEIGHTS, weights=None, sentinel=True):
+        self.shape = shape
+        self.w = weights if weights is not None else synth.make_weights(shape, seed=seed, n_layers=n_layers)
+        self.L = len(self.w["layers"])
+        self.max_seq = max_seq_len or shape.max_seq_len
+        self.om = oracle.OracleModel(shape, self.w, max_seq_len=self.max_seq)
+        self.gm = binding.Model(binding.make_config(shape, max_seq_len=self.max_seq, n_layers=self.L), self.w)
+        if sentinel:
+            self.gm.kv_fill(SENTINEL)
+        self.worst = {"hidden": 0.0, "logits": 0.0}
+        self.n_strict = 0
+        self.n_checked = 0
+
+    def close(self):
+        self.gm.close()
+
+    def compare(self, o, g_next, g_logits, where):
+        eh = rel_l2(self.gm.last_hidden(), o["hidden"][-1])
+        el = rel_l2(g_logits, o["logits"])
+        self.worst["hidden"] = max(self.worst["hidden"], eh)
+        self.worst["logits"] = max(self.worst["logits"], el)
+        assert eh <= REL_TOL, f"{where}: hidden rel-L2 {eh:.2e}"
+        assert el <= REL_TOL, f"{where}: logits rel-L2 {el:.2e}"
+        self.n_strict += check_token(g_next, o["logits"], where)
+        self.n_checked += 1
+
+    def prefill(self, tokens=None, embeds=None, where="prefill"):
+        o = self.om.prefill(tokens, embeds)
+        g_next, g_logits = self.gm.prefill(tokens, embeds)
+        self.compare(o, g_next, g_logits, where)
+        assert self.gm.kv_len == self.om.kv_len
+        return int(o["next"][0])
+
+    def decode(self, token, where):
+        o = self.om.decode_step(token)
+        g_next, g_logits = self.gm.decode_step(token, want_logits=True)
+        self.compare(o, g_next, g_logits, where)
+        assert self.gm.kv_len == self.om.kv_len
+        return int(o["next"][0])
+
+    def run(self, prompt, n_decode, embeds=None):
+        tok = self.prefill(prompt, embeds)
+        for i in range(n_decode):
+            tok = self.decode(tok, f"decode step {i}")
+        return tok
+
+    def check_kv(self, layers, positions):
+        """Values close to the oracle's, row p nearest to oracle row p, sentinel beyond kv_len."""
+        kd = self.shape.kv_dtype
+        n = self.om.kv_len
+        for l in layers:
+            for p in positions:
+                kg, vg = self.gm.kv_read(l, p)
+                if p >= n:
+                    assert (kg == SENTINEL).all() and (vg == SENTINEL).all(), f"write beyond kv_len at layer {l} pos {p}"
+                    continue
+                assert not (kg == SENTINEL).any() and not (vg == SENTINEL).any(), f"unwritten row layer {l} pos {p}"
+                kg = synth.from_bits(kg, kd).astype(np.float64); vg = synth.from_bits(vg, kd).astype(np.float64)
+                ko, vo = self.om.kv_read(l, p)
+                assert rel_l2(kg, ko) < 1e-2 and rel_l2(vg, vo) < 1e-2, (l, p, rel_l2(kg, ko), rel_l2(vg, vo))
+                for q in (p - 1, p + 1):
+                    if 0 <= q < n:
+                        kq, vq = self.om.kv_read(l, q)
+                        assert np.linalg.norm(kg - ko) < np.linalg.norm(kg - kq), f"K row {p} of layer {l} looks like row {q}"
+                        # V carries no position information: in layer 0 equal tokens give equal V rows
+                        if np.linalg.norm(vo - vq) > 1e-2 * np.linalg.norm(vo):
+                            assert np.linalg.norm(vg - vo) < np.linalg.norm(vg - vq), f"V row {p} of layer {l} looks like row {q}"
+
+
+# --------------------------------------------------------------------------------------------------
+# configs[0]: tiny fp16 decoder, 32 prompt tokens, 16 greedy tokens
+# --------------------------------------------------------------------------------------------------
+def test_tiny_config_full_parity_and_kv_indexing():
+    shape = synth.TINY
+    P = Pair(shape)
+    P.run(synth.make_prompt(shape, 32), 16)
+    assert P.gm.kv_len == 48
+    P.check_kv(range(shape.n_layers), range(shape.max_seq_len))
+    assert P.worst["logits"] < 1e-4  # fp16 weights, fp32 arithmetic: far inside the bar
+    P.close()
+
+
+TINY_BF16 = synth.TINY.with_(name="tiny-bf16-bias", weight_dtype=synth.BF16, kv_dtype=synth.BF16, qkv_bias=True,
+                             tie_embeddings=True, max_seq_len=200)
+TINY_MIXED = synth.TINY.with_(name="tiny-bf16-f16kv", weight_dtype=synth.BF16, kv_dtype=synth.F16, max_seq_len=80)
+TINY_D128 = synth.TINY.with_(name="tiny-d128-g3", n_q_heads=6, n_kv_heads=2, head_dim=128, hidden=384,
+                             weight_dtype=synth.BF16, kv_dtype=synth.BF16, qkv_bias=True, max_seq_len=150)
+
+
+@pytest.mark.parametrize("shape,n_prompt,n_decode", [
+    (TINY_BF16, 1, 3),      # single-token prompt
+    (TINY_BF16, 63, 4),     # one short of a key tile
+    (TINY_BF16, 129, 5),    # three query blocks with a ragged tail
+    (TINY_MIXED, 40, 4),    # bf16 weights with an f16 cache
+    (TINY_D128, 100, 6),    # head_dim 128, GQA group of 3
+    (synth.TINY.with_(name="tiny-g1", n_q_heads=2, n_kv_heads=2, hidden=128), 17, 3),  # plain MHA, g = 1
+    (synth.TINY.with_(name="tiny-g8", n_q_heads=8, n_kv_heads=1, hidden=512, head_dim=64), 33, 3),  # g = 8
+], ids=lambda v: getattr(v, "name", str(v)))
+def test_small_shape_variants(shape, n_prompt, n_decode):
+    P = Pair(shape, seed=99)
+    P.run(synth.make_prompt(shape, n_prompt, seed=3), n_decode)
+    n = n_prompt + n_decode
+    P.check_kv(range(shape.n_layers), sorted({0, n_prompt - 1, min(n_prompt, n - 1), n - 1, n, shape.max_seq_len - 1}))
+    P.close()
+
+
+def test_decode_only_from_empty_context():
+    """Eq. 4 alone: feeding the prompt one token at a time must give what the oracle gives."""
+    shape = TINY_BF16
+    P = Pair(shape)
+    for i, t in enumerate(synth.make_prompt(shape, 70)):
+        P.decode(int(t), f"token {i}")
+    P.check_kv(range(shape.n_layers), [0, 1, 63, 64, 69, 70, 71])
+    P.close()
+
+
+def test_prefill_then_decode_equals_full_prefill_on_gpu():
+    """The cache-exactness invariant of Eq. 3-4, checked on the GPU path against itself: logits of
+    position n-1 from prefill(n) and from prefill(k) + decode steps agree to rounding."""
+    shape = TINY_BF16
+    w = synth.make_weights(shape)
+    toks = synth.make_prompt(shape, 90)
+    gm = binding.Model(binding.make_config(shape), w)
+    _, full = gm.prefill(toks)
+    gm.kv_reset(0)
+    gm.prefill(toks[:37])
+    lg = None
+    for t in toks[37:]:
+        _, lg = gm.decode_step(int(t), want_logits=True)
+    # the two paths sum in different orders; a cache value that sits on a rounding tie may round apart
+    assert rel_l2(lg, full) < 2e-4
+    gm.close()
+
+
+def test_embedding_rows_then_tokens():
+    """VLM-shaped input on a small model: embedding rows (stand-in for a vision encoder's output) followed
+    by text tokens in one prefill, then decode."""
+    shape = TINY_D128
+    P = Pair(shape)
+    emb = synth.make_visual_embeds(shape, 70)
+    P.run(synth.make_prompt(shape, 20), 5, embeds=emb)
+    assert P.gm.kv_len == 95
+    P.close()
+
+
+def test_prefix_reuse_append_prefill():
+    """Section 3.9 / Eq. 5: keep the prefix KV, evaluate only the suffix."""
+    shape = TINY_BF16
+    P = Pair(shape)
+    toks = synth.make_prompt(shape, 150)
+    P.prefill(toks[:70], where="prefix")
+    first = P.prefill(toks[70:110], where="suffix A")
+    P.decode(first, "after suffix A")
+    P.om.kv_reset(70); P.gm.kv_reset(70)
+    assert P.gm.kv_len == 70
+    P.prefill(toks[110:150], where="suffix B on the kept prefix")
+    P.check_kv(range(shape.n_layers), [0, 69, 70, 109, 111])  # 110 holds stale data of the recycled slot
+    P.close()
+
+
+def test_device_chained_greedy_and_replay_determinism():
+    """token = -1 takes the previous greedy token on the device (Section 3.10: step parameters live in
+    GPU memory); replays are bit-identical; an explicit-token run reproduces the same stream."""
+    shape = synth.QWEN_0P5B.with_(name="0.5b-l4", max_seq_len=96)
+    w = synth.make_weights(shape, n_layers=4)
+    gm = binding.Model(binding.make_config(shape, n_layers=4), w)
+    toks = synth.make_prompt(shape, 24)
+
+    def chained():
+        gm.kv_reset(0)
+        first, _ = gm.prefill(toks)
+        out = [first]
+        for _ in range(20):
+            gm.decode_step(-1, sync=False)           # enqueue only
+        nxt, lg = gm.decode_step(-1, want_logits=True)
+        return first, nxt, lg
+
+    def explicit():
+        gm.kv_reset(0)
+        tok, _ = gm.prefill(toks)
+        lg = None
+        for _ in range(21):
+            tok, lg = gm.decode_step(tok, want_logits=True)
+        return tok, lg
+
+    f1, n1, l1 = chained()
+    f2, n2, l2 = chained()
+    n3, l3 = explicit()
+    assert gm.kv_len == 24 + 21
+    assert f1 == f2 and n1 == n2 == n3
+    assert np.array_equal(l1, l2) and np.array_equal(l1, l3)
+    gm.close()
+
+
+def test_error_paths_leave_state_unchanged():
+    shape = TINY_BF16.with_(max_seq_len=40)
+    w = synth.make_weights(shape)
+    gm = binding.Model(binding.make_config(shape), w)
+    E = binding.EdgefmError
+    with pytest.raises(E) as e:
+        gm.decode_step(-1)
+    assert e.value.status == binding.EDGEFM_ERR_STATE
+    with pytest.raises(E) as e:
+        gm.prefill(np.zeros(41, np.int32))
+    assert e.value.status == binding.EDGEFM_ERR_CONTEXT_OVERFLOW
+    for bad in (-1, shape.vocab):
+        with pytest.raises(E) as e:
+            gm.prefill(np.array([1, bad, 2], np.int32))
+        assert e.value.status == binding.EDGEFM_ERR_BAD_TOKEN
+    with pytest.raises(E) as e:
+        gm.decode_step(shape.vocab)
+    assert e.value.status == binding.EDGEFM_ERR_BAD_TOKEN
+    assert gm.kv_len == 0
+    toks = synth.make_prompt(shape, 39)
+    first, _ = gm.prefill(toks)
+    gm.decode_step(first)
+    assert gm.kv_len == 40
+    with pytest.raises(E) as e:
+        gm.decode_step(first)
+    assert e.value.status == binding.EDGEFM_ERR_CONTEXT_OVERFLOW
+    with pytest.raises(E) as e:
+        gm.kv_reset(41)
+    assert e.value.status == binding.EDGEFM_ERR_STATE
+    assert gm.kv_len == 40
+    gm.kv_reset(0)
+    again, _ = gm.prefill(toks)
+    assert again == first
+    # arena too small
+    import ctypes as C
+    import torch
+    cfg = binding.make_config(shape)
+    small = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    h = C.c_void_p()
+    wdev = torch.zeros(8, dtype=torch.int16, device="cuda:0")
+    tbl = (C.c_void_p * shape.n_layers)(*([wdev.data_ptr()] * shape.n_layers))
+    tp = C.cast(tbl, binding._PP)
+    ws = binding.edgefm_weights(wdev.data_ptr(), wdev.data_ptr(), wdev.data_ptr(), tp, tp, tp, tp, tp, tp, tp)
+    ptr = (small.data_ptr() + 255) // 256 * 256
+    st = gm.lib.edgefm_model_load(C.byref(cfg), C.byref(ws), C.c_void_p(ptr), 1 << 19, None, C.byref(h))
+    assert st == binding.EDGEFM_ERR_ARENA_TOO_SMALL and not h.value
+    gm.close()
+
+
+# --------------------------------------------------------------------------------------------------
+# decode attention over long injected contexts (split-context path at its real sizes)
+# --------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("ctx", [63, 64, 65, 1000, 4096, 8191])
+def test_decode_attention_over_injected_context_7b_width(ctx):
+    """7B-shaped width (28 q / 4 kv heads, d 128), depth truncated to 2 layers so that the oracle is fast;
+    the cache is filled with seeded random rows, then two decode steps run over it."""
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    rows = [synth.make_kv_rows(shape, l, ctx) for l in range(2)]
+    P.om.kv_inject(rows)
+    for l, (k, v) in enumerate(rows):
+        P.gm.kv_write(l, k, v)
+    P.gm.set_kv_len(ctx)
+    tok = P.decode(17, f"ctx {ctx} step 0")
+    P.decode(tok, f"ctx {ctx} step 1")
+    P.check_kv([0, 1], [ctx - 1, ctx, ctx + 1])
+
+
+_cache = {}
+
+
+def _get_7b_l2(shape):
+    if "p" not in _cache:
+        _cache["p"] = Pair(shape, n_layers=2, sentinel=False)
+    return _cache["p"]
+
+
+def test_long_prefill_7b_width_two_layers():
+    """Prefill GEMMs and flash attention at T = 2048 on the 7B-shaped width (depth 2), then the VLM-shaped
+    request: 1024 embedding rows + 64 tokens in one prefill and an 8-token greedy decode (configs[4])."""
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    P.om.kv_reset(0); P.gm.kv_reset(0)
+    t0 = time.time()
+    P.prefill(synth.make_prompt(shape, 2048), where="T=2048")
+    P.check_kv([0, 1], [0, 1, 1023, 2047])
+    P.om.kv_reset(0); P.gm.kv_reset(0)
+    P.run(synth.make_prompt(shape, 64), 8, embeds=synth.make_visual_embeds(shape, 1024))
+    assert P.gm.kv_len == 1024 + 64 + 8
+    print(f"long prefill checks {time.time() - t0:.1f}s worst {P.worst}")
+    P.close()
+    _cache.clear()
+
+
+# --------------------------------------------------------------------------------------------------
+# configs[1..3] at full depth
+# --------------------------------------------------------------------------------------------------
+def test_qwen_0p5b_config_128_prompt_256_decode():
+    shape = synth.QWEN_0P5B
+    P = Pair(shape)
+    P.run(synth.make_prompt(shape, 128), 256)
+    P.check_kv([0, 11, 23], [0, 127, 128, 383])
+    print(f"0.5B worst {P.worst} strict tokens {P.n_strict}/{P.n_checked}")
+    assert P.n_strict >= P.n_checked // 2
+    P.close()
+
+
+def test_qwen_1p5b_config_512_prompt_128_decode():
+    shape = synth.QWEN_1P5B
+    P = Pair(shape)
+    P.run(synth.make_prompt(shape, 512), 128)
+    P.check_kv([0, 27], [0, 511, 512, 639])
+    print(f"1.5B worst {P.worst} strict tokens {P.n_strict}/{P.n_checked}")
+    P.close()
+
+
+def test_qwen_7b_config_prefill_128_decode_and_long_context():
+    """Full-depth 7B-shaped model: prefill 128 + 4 decode steps, then decode steps over an injected context
+    of 4096 positions (28 layers) -- the launch configuration bench.py times."""
+    shape = synth.QWEN_7B.with_(max_seq_len=4096 + 16)
+    t0 = time.time()
+    P = Pair(shape, sentinel=False)
+    print(f"7B build {time.time() - t0:.1f}s", flush=True)
+    P.run(synth.make_prompt(shape, 128), 4)
+    P.check_kv([0, 27], [0, 127, 131])
+    print(f"7B prefill+decode {time.time() - t0:.1f}s worst {P.worst}", flush=True)
+    ctx = 4096
+    rows = [synth.make_kv_rows(shape, l, ctx) for l in range(shape.n_layers)]
+    P.om.kv_inject(rows)
+    for l, (k, v) in enumerate(rows):
+        P.gm.kv_write(l, k, v)
+    P.gm.set_kv_len(ctx)
+    tok = P.decode(5, "ctx 4096 step 0")
+    P.decode(tok, "ctx 4096 step 1")
+    print(f"7B total {time.time() - t0:.1f}s worst {P.worst} strict {P.n_strict}/{P.n_checked}", flush=True)
+    P.close()
