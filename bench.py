@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the batch-1 decoder hot path on one MI355X.
+
+A "step" is one request of the Qwen2.5-7B-shaped workload (random bf16 weights, synthetic prompt):
+reset the KV slot, prefill PROMPT tokens, then DECODE greedy decode steps chained on the device.
+The headline value is the decode latency in ms/token (BASELINE metric); TTFT, the achieved HBM
+bandwidth of the decode step and the prefill TFLOP/s ride along in the same JSON line, together with
+  * "roofline":     the dominant decode kernel (gate/up GEMV) timed alone with HIP events,
+  * "cpu_baseline": the CPU oracle timed on this host on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--prompt T] [--decode N] [--shape NAME]
+
+Inputs are resident in HBM before the timed region starts (weights are uploaded once at load).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 / f16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def prefill_flops(shape, T):
+    """2*T*P_layers + causal attention (QK^T and PV over the lower triangle) + last-row lm_head."""
+    H, I = shape.hidden, shape.intermediate
+    per_tok = shape.n_layers * (shape.qkv_rows * H + H * shape.q_dim + 3 * I * H)
+    attn = shape.n_layers * 4 * shape.n_q_heads * shape.head_dim * T * (T + 1) // 2
+    return 2 * T * per_tok + attn + 2 * shape.vocab * H
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--prompt", type=int, default=1024)
+    ap.add_argument("--decode", type=int, default=64)
+    ap.add_argument("--shape", default="qwen2.5-7b-shaped")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build is the single-GPU hot path of a single-request system; "
+            "--gpus N with N > 1 is not supported (one request never spans GPUs).")
+        return 2
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2604_27476_amd import binding
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 2
+    binding.load_library()  # fails loudly if libedgefm.so is missing
+
+    shape0 = synth.SHAPES[args.shape]
+    T, N = args.prompt, args.decode
+    shape = shape0.with_(max_seq_len=T + N + 8)
+    t0 = time.time()
+    w = synth.make_weights(shape)
+    log(f"[bench] weights {shape.name}: {shape.weight_bytes_per_token() / 1e9:.2f} GB/token, generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    gm = binding.Model(binding.make_config(shape), w)
+    log(f"[bench] uploaded + loaded in {time.time() - t0:.1f}s, arena {gm.arena_bytes / 1e9:.1f} GB")
+    prompt = synth.make_prompt(shape, T)
+    stream = gm.stream
+
+    def request():
+        gm.kv_reset(0)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e2 = torch.cuda.Event(enable_timing=True)
+        h0 = time.perf_counter()
+        e0.record(stream)
+        first, _ = gm.prefill(prompt, want_logits=False)     # synchronises: the first token is on the host
+        h1 = time.perf_counter()
+        e1.record(stream)
+        for _ in range(N - 1):
+            gm.decode_step(-1, sync=False)                   # device-chained greedy decode, graph replays
+        last, _ = gm.decode_step(-1)                         # the N-th step returns its token: synchronises
+        e2.record(stream)
+        stream.synchronize()
+        h2 = time.perf_counter()
+        return {"ttft_ms": (h1 - h0) * 1e3, "ttft_dev_ms": e0.elapsed_time(e1), "decode_ms": e1.elapsed_time(e2),
+                "decode_host_ms": (h2 - h1) * 1e3, "total_ms": (h2 - h0) * 1e3, "first": first, "last": last}
+
+    for _ in range(args.warmup):
+        request()
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    runs = [request() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_begin
+    assert len({(r["first"], r["last"]) for r in runs}) == 1, "replays of the same request disagree"
+    assert gm.kv_len == T + N
+
+    dec_ms = float(np.mean([r["decode_host_ms"] for r in runs])) / N
+    dec_dev_ms = float(np.mean([r["decode_ms"] for r in runs])) / N
+    ttft = float(np.mean([r["ttft_ms"] for r in runs]))
+    # algorithmic bytes of one decode step: every parameter once + the KV rows of the context (mean context)
+    mean_ctx = T + (N - 1) / 2.0
+    step_bytes = shape.weight_bytes_per_token() + shape.kv_bytes_per_context_token() * mean_ctx
+    dec_gbps = step_bytes / (dec_ms * 1e-3) / 1e9
+    pf_tflops = prefill_flops(shape, T) / (ttft * 1e-3) / 1e12
+
+    # ---- dominant kernel alone: gate/up GEMV, cycling through the layers' weights -----------------
+    reps = 20 * shape.n_layers
+    gm.launch_op(binding.EDGEFM_OP_GATEUP, -1, shape.n_layers)  # warm
+    stream.synchronize()
+    a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    gm.launch_op(binding.EDGEFM_OP_GATEUP, -1, reps)
+    b.record(stream)
+    stream.synchronize()
+    k_us = a.elapsed_time(b) * 1e3 / reps
+    k_bytes = 2 * shape.intermediate * shape.hidden * 2 + shape.hidden * 4 + shape.hidden * 2 + shape.intermediate * 4
+    k_gbps = k_bytes / (k_us * 1e-6) / 1e9
+    roofline = {"kernel": "k_gateup (gate/up GEMV + RMSNorm prologue + SwiGLU epilogue)", "bound": "hbm",
+                "achieved": round(k_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": k_bytes, "us_per_launch": round(k_us, 2)}
+
+    # ---- CPU oracle on this host: a few decode steps of the same model at the same context --------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        om = oracle.OracleModel(shape, w)
+        om.kv_inject([synth.make_kv_rows(shape, l, T) for l in range(shape.n_layers)])
+        tok = int(runs[0]["first"])
+        om.decode_step(tok, logits="none", want_hidden=False)  # touch the weights once
+        n_cpu, t_cpu = 0, time.perf_counter()
+        while n_cpu < 3 or (time.perf_counter() - t_cpu < 12.0 and n_cpu < 64):
+            tok = int(om.decode_step(tok, want_hidden=False)["next"][0])
+            n_cpu += 1
+        t_cpu = time.perf_counter() - t_cpu
+        cpu = {"value": round(t_cpu / n_cpu * 1e3, 2), "unit": "ms/token", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"{n_cpu} decode steps of the same {shape.name} model over an injected "
+               f"random context of {T} positions (fp64 C oracle, OpenMP)"}
+
+    out = {
+        "metric": "decode_ms_per_token", "value": round(dec_ms, 4), "unit": "ms/token", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(t_total / args.steps * 1e3, 3),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}: prefill {T} + {N} greedy decode steps, batch 1",
+                   "prompt_tokens": T, "decode_steps": N, "kv_dtype": "bf16"},
+        "decode_ms_per_token_device": round(dec_dev_ms, 4),
+        "decode_hbm_GBps": round(dec_gbps, 1), "decode_frac_of_hbm_peak": round(dec_gbps / HBM_PEAK_GBPS, 4),
+        "decode_bytes_per_token": int(step_bytes),
+        "ttft_ms": round(ttft, 3), "ttft_device_ms": round(float(np.mean([r["ttft_dev_ms"] for r in runs])), 3),
+        "prefill_TFLOPs": round(pf_tflops, 1), "prefill_frac_of_mfma_peak": round(pf_tflops / MFMA_PEAK_TFLOPS, 4),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    gm.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

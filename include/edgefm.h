@@ -137,7 +137,9 @@ int edgefm_debug_last_hidden(edgefm_model *m, float *hidden_host);
  * prefill again before using the model for inference.  Requires kv_len >= 1. */
 typedef enum {
     EDGEFM_OP_QKV = 0, EDGEFM_OP_ATTN = 1, EDGEFM_OP_OPROJ = 2, EDGEFM_OP_GATEUP = 3, EDGEFM_OP_DOWN = 4,
-    EDGEFM_OP_LMHEAD = 5
+    EDGEFM_OP_LMHEAD = 5,
+    EDGEFM_OP_COPY = 6 /* plain copy of min(gate/up weight bytes, max_seq_len*hidden*4) bytes: a kernel of
+                          known HBM traffic (read n, write n) for calibrating hardware byte counters */
 } edgefm_op;
 int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat);
 

@@ -79,8 +79,14 @@ def _lib(kind: str = "f64"):
         lib.oracle_argmax.restype = C.c_int32
         lib.oracle_argmax.argtypes = [C.c_void_p, C.c_uint32]
         lib.oracle_real_bytes.restype = C.c_int
+        lib.oracle_num_threads.restype = C.c_int
         _loaded[kind] = lib
     return _loaded[kind]
+
+
+def num_threads() -> int:
+    """Threads the oracle's OpenMP loops use on this host."""
+    return _lib().oracle_num_threads()
 
 
 def _p(a):

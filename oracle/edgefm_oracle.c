@@ -27,6 +27,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #ifndef ORACLE_REAL
 #define ORACLE_REAL double
@@ -410,3 +413,12 @@ int oracle_forward(oracle_model *m, const uint16_t *embeds, uint32_t n_embeds, c
 }
 
 int oracle_real_bytes(void) { return (int)sizeof(real); }
+
+/* threads the OpenMP loops will use */
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

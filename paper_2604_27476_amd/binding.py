@@ -19,7 +19,8 @@ EDGEFM_F16, EDGEFM_BF16 = 1, 2
 EDGEFM_OK = 0
 EDGEFM_ERR_INVALID_ARG, EDGEFM_ERR_ARENA_TOO_SMALL, EDGEFM_ERR_CONTEXT_OVERFLOW = -1, -2, -3
 EDGEFM_ERR_BAD_TOKEN, EDGEFM_ERR_STATE, EDGEFM_ERR_HIP = -4, -5, -6
-EDGEFM_OP_QKV, EDGEFM_OP_ATTN, EDGEFM_OP_OPROJ, EDGEFM_OP_GATEUP, EDGEFM_OP_DOWN, EDGEFM_OP_LMHEAD = range(6)
+EDGEFM_OP_QKV, EDGEFM_OP_ATTN, EDGEFM_OP_OPROJ, EDGEFM_OP_GATEUP, EDGEFM_OP_DOWN, EDGEFM_OP_LMHEAD, \
+    EDGEFM_OP_COPY = range(7)
 
 EXPORTS = [
     "edgefm_query_sizes", "edgefm_model_load", "edgefm_prefill", "edgefm_decode_step", "edgefm_kv_reset",

@@ -46,41 +46,58 @@ __device__ __forceinline__ void stage_vec(const float *__restrict__ x, const uin
 
 // ------------------------------------------------------------------------------------------------
 // One wave computes NR dot products of length K = 8*nvec against the staged vector.
-// Each lane keeps up to U*NR independent 16-byte loads in flight before the FMA chain.
+// Each lane keeps up to U*NR independent 16-byte loads in flight before the FMA chain.  The loads of
+// the first chunk can be issued ahead of time (wave_prefetch), e.g. before the workgroup stages its
+// activation vector: weights never depend on activations.
 // ------------------------------------------------------------------------------------------------
+template <int NR, int U> struct Chunk {
+    u32x4 w[U][NR];
+};
+
+template <int NR, int U>
+__device__ __forceinline__ void chunk_load(Chunk<NR, U> &c, const uint16_t *const (&rows)[NR], int v0, int nvec) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int v = v0 + u * WAVE;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            if (v < nvec) c.w[u][r] = ld_stream16(rows[r] + (size_t)v * 8);
+            else c.w[u][r] = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+}
+
+template <int DT, int NR, int U>
+__device__ __forceinline__ void chunk_fma(const Chunk<NR, U> &c, const float4 *xs, int v0, int nvec, float (&acc)[NR]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int v = v0 + u * WAVE;
+        if (v < nvec) {
+            const float4 a = xs[v], b = xs[nvec + v];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                float f[8];
+                unpack8<DT>(c.w[u][r], f);
+                float s = acc[r];
+                s = fmaf(f[0], a.x, s); s = fmaf(f[1], a.y, s); s = fmaf(f[2], a.z, s); s = fmaf(f[3], a.w, s);
+                s = fmaf(f[4], b.x, s); s = fmaf(f[5], b.y, s); s = fmaf(f[6], b.z, s); s = fmaf(f[7], b.w, s);
+                acc[r] = s;
+            }
+        }
+    }
+}
+
+// `pre` holds the chunk starting at v0 = lane if have_pre (in flight or arrived); it is clobbered.
 template <int DT, int NR, int U>
 __device__ __forceinline__ void wave_dots(const uint16_t *const (&rows)[NR], const float4 *xs, int nvec, int lane,
-                                          float (&out)[NR]) {
+                                          float (&out)[NR], Chunk<NR, U> &pre, bool have_pre) {
     float acc[NR];
 #pragma unroll
     for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-    for (int v0 = lane; v0 < nvec; v0 += WAVE * U) {
-        u32x4 w[U][NR];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int v = v0 + u * WAVE;
-#pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                if (v < nvec) w[u][r] = ld_stream16(rows[r] + (size_t)v * 8);
-                else w[u][r] = u32x4{0u, 0u, 0u, 0u};
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int v = v0 + u * WAVE;
-            if (v < nvec) {
-                const float4 a = xs[v], b = xs[nvec + v];
-#pragma unroll
-                for (int r = 0; r < NR; ++r) {
-                    float f[8];
-                    unpack8<DT>(w[u][r], f);
-                    float s = acc[r];
-                    s = fmaf(f[0], a.x, s); s = fmaf(f[1], a.y, s); s = fmaf(f[2], a.z, s); s = fmaf(f[3], a.w, s);
-                    s = fmaf(f[4], b.x, s); s = fmaf(f[5], b.y, s); s = fmaf(f[6], b.z, s); s = fmaf(f[7], b.w, s);
-                    acc[r] = s;
-                }
-            }
-        }
+    for (int v0 = lane; v0 < nvec; v0 += WAVE * U) {  // one register buffer, reused for every chunk
+        if (!have_pre) chunk_load<NR, U>(pre, rows, v0, nvec);
+        have_pre = false;
+        chunk_fma<DT, NR, U>(pre, xs, v0, nvec, acc);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) out[r] = wave_sum(acc[r]);
@@ -111,16 +128,23 @@ k_qkv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const u
       int H, int nq, int nkv, int d, int max_seq, float eps) {
     extern __shared__ float4 smem[];
     __shared__ float red[32];
-    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int half = d >> 1, n_units = (nq + 2 * nkv) * half, nvec = H >> 3;
+    const int unit0 = blockIdx.x * nw + wave;
+    Chunk<2, 7> pre;
+    if (unit0 < n_units) {  // weights first: they do not depend on the activations
+        const int hh = unit0 / half, r0 = hh * d + (unit0 - hh * half);
+        const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)(r0 + half) * H};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     const int pos = d_pos[0];
-    for (int unit = blockIdx.x * nw + wave; unit < n_units; unit += gridDim.x * nw) {
+    for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int hh = unit / half, i = unit - hh * half;
         const int r0 = hh * d + i, r1 = r0 + half;
         const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)r1 * H};
         float o[2];
-        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        wave_dots<DT, 2, 7>(rows, smem, nvec, lane, o, pre, unit == unit0);
         if (lane == 0) {
             float v0 = o[0], v1 = o[1];
             if (bias) {
@@ -158,14 +182,20 @@ k_gemv_resid(const uint16_t *__restrict__ W, const float *__restrict__ vec, floa
              int K) {
     extern __shared__ float4 smem[];
     __shared__ float red[32];
-    stage_vec<DT, false>(vec, nullptr, K, 0.f, smem, red);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int n_units = (rows_n + 1) >> 1, nvec = K >> 3;
-    for (int unit = blockIdx.x * nw + wave; unit < n_units; unit += gridDim.x * nw) {
+    const int unit0 = blockIdx.x * nw + wave;
+    Chunk<2, 7> pre;
+    if (unit0 < n_units) {
+        const uint16_t *rows[2] = {W + (size_t)(2 * unit0) * K, W + (size_t)min(2 * unit0 + 1, rows_n - 1) * K};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+    stage_vec<DT, false>(vec, nullptr, K, 0.f, smem, red);
+    for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int r0 = 2 * unit, r1 = min(2 * unit + 1, rows_n - 1);
         const uint16_t *rows[2] = {W + (size_t)r0 * K, W + (size_t)r1 * K};
         float o[2];
-        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        wave_dots<DT, 2, 7>(rows, smem, nvec, lane, o, pre, unit == unit0);
         if (lane == 0) {
             x[r0] += o[0];
             if (r1 != r0) x[r1] += o[1];
@@ -182,13 +212,19 @@ k_gateup(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
          float *__restrict__ h, int H, int I, float eps) {
     extern __shared__ float4 smem[];
     __shared__ float red[32];
-    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int nvec = H >> 3;
-    for (int j = blockIdx.x * nw + wave; j < I; j += gridDim.x * nw) {
+    const int j0 = blockIdx.x * nw + wave;
+    Chunk<2, 7> pre;
+    if (j0 < I) {
+        const uint16_t *rows[2] = {W + (size_t)j0 * H, W + (size_t)(I + j0) * H};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+    stage_vec<DT, true>(x, gain, H, eps, smem, red);
+    for (int j = j0; j < I; j += gridDim.x * nw) {
         const uint16_t *rows[2] = {W + (size_t)j * H, W + (size_t)(I + j) * H};
         float o[2];
-        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        wave_dots<DT, 2, 7>(rows, smem, nvec, lane, o, pre, j == j0);
         if (lane == 0) h[j] = o[0] / (1.0f + expf(-o[0])) * o[1];
     }
 }
@@ -206,9 +242,16 @@ k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
     __shared__ float red[32];
     __shared__ float bv[16];
     __shared__ int bi[16];
-    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int nvec = H >> 3;
+    const int n_units = (V + 1) >> 1;
+    const int unit0 = blockIdx.x * nw + wave;
+    Chunk<2, 7> pre;
+    if (unit0 < n_units) {
+        const uint16_t *rows[2] = {W + (size_t)(2 * unit0) * H, W + (size_t)min(2 * unit0 + 1, V - 1) * H};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     if (blockIdx.x == 0) {  // export the final hidden state (the tensor the parity tolerance is stated on)
         for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
             reinterpret_cast<float4 *>(hidden)[2 * v] = smem[v];
@@ -217,12 +260,11 @@ k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
     }
     float best = -INFINITY;
     int best_i = 0x7fffffff;
-    const int n_units = (V + 1) >> 1;
-    for (int unit = blockIdx.x * nw + wave; unit < n_units; unit += gridDim.x * nw) {
+    for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int r0 = 2 * unit, r1 = min(2 * unit + 1, V - 1);
         const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)r1 * H};
         float o[2];
-        wave_dots<DT, 2, 8>(rows, smem, nvec, lane, o);
+        wave_dots<DT, 2, 7>(rows, smem, nvec, lane, o, pre, unit == unit0);
         if (lane == 0) {
             logits[r0] = o[0];
             if (o[0] > best) { best = o[0]; best_i = r0; }   // rows visited in increasing order per wave
@@ -248,10 +290,11 @@ k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
 // finish: greedy token = argmax over the per-block partials (lowest index on ties); feed it back as
 // the next step's input token and advance the position (the "KV cache management kernel" of
 // Section 3.10 that keeps the decode step a fixed graph).
-__global__ void k_finish(const float *__restrict__ part_val, const int *__restrict__ part_idx, int n_part,
-                         int *__restrict__ d_next, int *__restrict__ d_token, int *__restrict__ d_pos, int advance) {
-    __shared__ float sv[256];
-    __shared__ int si[256];
+__global__ void __launch_bounds__(256)
+k_finish(const float *__restrict__ part_val, const int *__restrict__ part_idx, int n_part,
+         int *__restrict__ d_next, int *__restrict__ d_token, int *__restrict__ d_pos, int advance) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
     float best = -INFINITY;
     int best_i = 0x7fffffff;
     for (int p = threadIdx.x; p < n_part; p += blockDim.x) {
@@ -259,11 +302,19 @@ __global__ void k_finish(const float *__restrict__ part_val, const int *__restri
         const int i = part_idx[p];
         if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
     }
-    sv[threadIdx.x] = best;
-    si[threadIdx.x] = best_i;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float v = __shfl_xor(best, o, WAVE);
+        const int i = __shfl_xor(best_i, o, WAVE);
+        if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
+    }
+    if ((threadIdx.x & 63) == 0) {
+        sv[threadIdx.x >> 6] = best;
+        si[threadIdx.x >> 6] = best_i;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int t = 1; t < (int)blockDim.x; ++t)
+        for (int t = 1; t < 4; ++t)
             if (sv[t] > best || (sv[t] == best && si[t] < best_i)) { best = sv[t]; best_i = si[t]; }
         if (best_i == 0x7fffffff) best_i = 0;  // all logits NaN/-inf: still return a valid id
         d_next[0] = best_i;
@@ -273,6 +324,11 @@ __global__ void k_finish(const float *__restrict__ part_val, const int *__restri
 }
 
 __global__ void k_set_int(int *p, int v) { p[0] = v; }
+// plain 16-byte copy: the reference kernel of known traffic used to calibrate HBM byte counters
+__global__ void __launch_bounds__(256) k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t nvec) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
 __global__ void k_fill_u16(uint16_t *p, size_t n, uint16_t v) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -299,7 +355,9 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
     constexpr int UR = 4;            // loads in flight per lane (K and V each)
     constexpr int NW = 4;
     constexpr int PS = D + 2;        // partial record: m, l, acc[D]
+    constexpr int MAX_S = 64;        // launchers never use more context slices
     __shared__ float wstate[NW][GQ][PS];
+    __shared__ float sm[GQ][MAX_S], sl[GQ][MAX_S];
     __shared__ uint32_t ticket_s;
 
     const int kvh = blockIdx.y, s = blockIdx.x;
@@ -412,7 +470,10 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         }
     }
     __syncthreads();
-    // merge the waves: thread (h, i) -> partial record of this context slice
+    // merge the waves: thread (h, i) -> partial record of this context slice.  Records are exchanged
+    // between workgroups (possibly on different XCDs, whose L2s are not coherent with each other) with
+    // agent-scope atomic stores and loads: they are performed at the device-coherent level, so no L2
+    // write-back / invalidate is needed around the arrival counter.
     float *prec = part + ((size_t)(kvh * GQ) * S + s) * PS;  // record of head h at + h*S*PS
     for (int idx = threadIdx.x; idx < GQ * D; idx += blockDim.x) {
         const int h = idx / D, i = idx - h * D;
@@ -428,33 +489,53 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         }
         float *rec = prec + (size_t)h * S * PS;
         if (i == 0) {
-            rec[0] = mt;
-            rec[1] = lt;
+            __hip_atomic_store(rec + 0, mt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(rec + 1, lt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        rec[2 + i] = at;
+        __hip_atomic_store(rec + 2 + i, at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // last slice to finish merges all slices of this KV head
-    __threadfence();
+    // every thread waits for its own stores, then one thread takes an arrival ticket
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0)
-        ticket_s = __hip_atomic_fetch_add(&counters[kvh], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        ticket_s = __hip_atomic_fetch_add(&counters[kvh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (uint32_t)(n_active - 1)) return;
-    __threadfence();
+    // the last slice to arrive combines all slices of this KV head, in index order (reproducible)
+    for (int idx = threadIdx.x; idx < GQ * n_active; idx += blockDim.x) {
+        const int h = idx / n_active, t = idx - h * n_active;
+        const float *rec = part + ((size_t)(kvh * GQ + h) * S + t) * PS;
+        sm[h][t] = __hip_atomic_load(rec + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sl[h][t] = __hip_atomic_load(rec + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
     for (int idx = threadIdx.x; idx < GQ * D; idx += blockDim.x) {
         const int h = idx / D, i = idx - h * D;
-        const float *rec = part + ((size_t)(kvh * GQ + h) * S) * PS;
+        const float *rec = part + ((size_t)(kvh * GQ + h) * S) * PS + 2 + i;
         float mt = NEG_BIG;
-        for (int t = 0; t < n_active; ++t) mt = fmaxf(mt, __builtin_nontemporal_load(rec + (size_t)t * PS));
+        for (int t = 0; t < n_active; ++t) mt = fmaxf(mt, sm[h][t]);
         float lt = 0.f, at = 0.f;
-        for (int t = 0; t < n_active; ++t) {
-            const float c = __expf(__builtin_nontemporal_load(rec + (size_t)t * PS) - mt);
-            lt += __builtin_nontemporal_load(rec + (size_t)t * PS + 1) * c;
-            at += __builtin_nontemporal_load(rec + (size_t)t * PS + 2 + i) * c;
+        int t = 0;
+        for (; t + 4 <= n_active; t += 4) {
+            float a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                a[u] = __hip_atomic_load(rec + (size_t)(t + u) * PS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float c = __expf(sm[h][t + u] - mt);
+                lt += sl[h][t + u] * c;
+                at += a[u] * c;
+            }
+        }
+        for (; t < n_active; ++t) {
+            const float c = __expf(sm[h][t] - mt);
+            lt += sl[h][t] * c;
+            at += __hip_atomic_load(rec + (size_t)t * PS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * c;
         }
         o[(size_t)(kvh * GQ + h) * D + i] = at / lt;
     }
-    if (threadIdx.x == 0) counters[kvh] = 0;  // ready for the next launch (stream order)
+    if (threadIdx.x == 0) __hip_atomic_store(&counters[kvh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ================================================================================================
@@ -471,8 +552,8 @@ static GemvGrid gemv_grid(int n_units, int n_cu, size_t lds_bytes) {
     int waves = clampi(per_cu, 4, 16);
     (void)lds_bytes;
     int blocks = (n_units + waves - 1) / waves;
-    // many units per CU: two workgroups per CU, each wave loops
-    if (blocks > 2 * n_cu) blocks = 2 * n_cu;
+    // many units per CU: one 16-wave workgroup per CU, each wave loops over its units
+    if (blocks > n_cu) blocks = n_cu;
     GemvGrid g = {blocks, waves * 64};
     return g;
 }
@@ -564,6 +645,11 @@ void launch_finish(const float *part_val, const int *part_idx, int n_part, int *
 }
 
 void launch_set_int(int *p, int v, hipStream_t st) { hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, st, p, v); }
+
+void launch_copy16(const void *src, void *dst, size_t bytes, hipStream_t st) {
+    hipLaunchKernelGGL(k_copy16, dim3(2048), dim3(256), 0, st, static_cast<const u32x4 *>(src),
+                       static_cast<u32x4 *>(dst), bytes / 16);
+}
 
 void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st) {
     size_t blocks = (n + 255) / 256;

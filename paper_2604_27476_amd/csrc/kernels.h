@@ -53,6 +53,7 @@ void launch_finish(const float *part_val, const int *part_idx, int n_part, int *
                    int advance, hipStream_t st);
 void launch_set_int(int *p, int v, hipStream_t st);
 void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st);
+void launch_copy16(const void *src, void *dst, size_t bytes, hipStream_t st);
 int lmhead_blocks(const Dims &D, const Geo &G);
 
 // ------------------------------------------------------------------ prefill (m = T)

@@ -531,7 +531,7 @@ int edgefm_debug_last_hidden(edgefm_model *m, float *hidden_host) {
 }
 
 int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) {
-    if (!m || op < 0 || op > EDGEFM_OP_LMHEAD || layer >= (int)m->cfg.n_layers) return EDGEFM_ERR_INVALID_ARG;
+    if (!m || op < 0 || op > EDGEFM_OP_COPY || layer >= (int)m->cfg.n_layers) return EDGEFM_ERR_INVALID_ARG;
     if (m->kv_len < 1) return EDGEFM_ERR_STATE;
     const Dims &D = m->D;
     hipStream_t st = m->stream;
@@ -559,6 +559,14 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) 
                               m->at<float>(m->L.hidden), m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx),
                               &m->n_part, st);
                 break;
+            case EDGEFM_OP_COPY: {  // layer l's gate/up weights -> its f16 prefill copy region and back is not
+                                    // wanted: copy into the prefill scratch instead (same size class)
+                size_t bytes = (size_t)2 * D.I * D.H * 2;
+                const size_t room = (size_t)D.max_seq * D.H * 4;  // X scratch
+                if (bytes > room) bytes = room / 16 * 16;
+                launch_copy16(W.w_gate_up, m->at<char>(m->L.X), bytes, st);
+                break;
+            }
         }
     }
     launch_set_int(m->d_pos(), (int)m->kv_len, st);

@@ -1,0 +1,52 @@
+#!/usr/bin/env python3
+"""Launch single decode-stage kernels of libedgefm in isolation, for use under rocprofv3.
+
+    rocprofv3 --kernel-trace --stats -d OUT -- python3 paper_2604_27476_amd/profile_ops.py --ops gateup,copy
+    rocprofv3 --pmc FETCH_SIZE -d OUT -- python3 paper_2604_27476_amd/profile_ops.py --ops gateup,copy
+    rocprofv3 --pmc WRITE_SIZE -d OUT -- python3 paper_2604_27476_amd/profile_ops.py --ops gateup,copy
+
+Each requested op is launched `--repeat` times, cycling through the layers so that no launch re-reads the
+weights of the previous one.  `copy` is a plain copy kernel of known size (it reads and writes the
+byte count printed below): the hardware byte counters of the other kernels are scaled by what they
+report for it.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+OPS = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lmhead": 5, "copy": 6}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--shape", default="qwen2.5-7b-shaped")
+    ap.add_argument("--ops", default="gateup,copy")
+    ap.add_argument("--repeat", type=int, default=56)
+    ap.add_argument("--context", type=int, default=1024)
+    ap.add_argument("--layers", type=int, default=0, help="truncate the depth (0 = full)")
+    args = ap.parse_args()
+    import synth
+    from paper_2604_27476_amd import binding
+    shape = synth.SHAPES[args.shape].with_(max_seq_len=args.context + 16)
+    L = args.layers or shape.n_layers
+    w = synth.make_weights(shape, n_layers=L)
+    gm = binding.Model(binding.make_config(shape, n_layers=L), w)
+    gm.prefill(synth.make_prompt(shape, args.context), want_logits=False)
+    copy_bytes = min(2 * shape.intermediate * shape.hidden * 2, shape.max_seq_len * shape.hidden * 4) // 16 * 16
+    print(f"copy kernel: reads {copy_bytes} bytes and writes {copy_bytes} bytes per launch", flush=True)
+    for name in args.ops.split(","):
+        gm.launch_op(OPS[name], -1, args.repeat)
+        gm.synchronize()
+        print(f"launched {name} x {args.repeat}", flush=True)
+    gm.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
