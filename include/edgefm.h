@@ -130,6 +130,13 @@ int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n);
 /* Final-norm output ("final hidden state") of the most recent prefill / decode step: [hidden] float. */
 int edgefm_debug_last_hidden(edgefm_model *m, float *hidden_host);
 
+/* Stage time stamps of the most recent fused decode step (only when the library was loaded with the
+ * environment variable EDGEFM_TRACE=1 and the shape uses the fused step kernel, else EDGEFM_ERR_STATE):
+ * for stage s of the step (per layer: QKV, attention, O projection, gate/up, down; then lm_head), written by
+ * workgroup 0: stamps[4s+0] stage entry, +1 after the grid barrier, +2 after staging the activation
+ * vector, +3 after the last unit.  Ticks of the constant 100 MHz device clock.  At most n values. */
+int edgefm_debug_stage_trace(edgefm_model *m, uint64_t *stamps_host, uint32_t n);
+
 /* Enqueue `repeat` launches of one decode-stage kernel on the model's stream, without synchronising
  * (the caller brackets the call with HIP events to time a single kernel, Section 3.4 profile-guided
  * workflow).  layer < 0 cycles through the layers so that no launch re-reads the previous one's

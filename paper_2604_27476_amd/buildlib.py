@@ -6,8 +6,8 @@ import subprocess
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_DIR, "csrc")
-_SOURCES = ["model.hip", "decode_kernels.hip", "prefill_kernels.hip"]
-_HEADERS = ["common.h", "kernels.h", os.path.join("..", "..", "include", "edgefm.h")]
+_SOURCES = ["model.hip", "decode_kernels.hip", "decode_mega.hip", "prefill_kernels.hip"]
+_HEADERS = ["common.h", "gemv.h", "kernels.h", os.path.join("..", "..", "include", "edgefm.h")]
 
 
 def lib_path() -> str:

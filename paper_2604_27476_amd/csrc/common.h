@@ -68,10 +68,14 @@ template <int DT> __device__ __forceinline__ uint32_t down2(float lo, float hi) 
 // ---- loads ---------------------------------------------------------------------------------------
 // 128-bit streaming load: weights are read exactly once per step, so they should not displace the
 // activations and KV tiles that live in L2.
-__device__ __forceinline__ u32x4 ld_stream16(const void *p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+// Every pointer this library dereferences on the device is global memory; saying so keeps loads through
+// pointers that were themselves read from memory on the global (not the flat) path.
+typedef const __attribute__((address_space(1))) u32x4 *gptr16;
+__device__ __forceinline__ gptr16 as_global16(const void *p) {
+    return reinterpret_cast<gptr16>(reinterpret_cast<uintptr_t>(p));
 }
-__device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x4 ld_stream16(const void *p) { return __builtin_nontemporal_load(as_global16(p)); }
+__device__ __forceinline__ u32x4 ld16(const void *p) { return *as_global16(p); }
 
 // ---- wave / block reductions -------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {

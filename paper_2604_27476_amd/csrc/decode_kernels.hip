@@ -4,6 +4,7 @@
 // Everything that changes from step to step (position, token) is read from device memory so that the
 // whole step can be replayed as one captured graph (Section 3.10).
 #include "common.h"
+#include "gemv.h"
 #include "kernels.h"
 
 namespace efm {
@@ -42,65 +43,6 @@ __device__ __forceinline__ void stage_vec(const float *__restrict__ x, const uin
         xs[nvec + v] = b;
     }
     __syncthreads();
-}
-
-// ------------------------------------------------------------------------------------------------
-// One wave computes NR dot products of length K = 8*nvec against the staged vector.
-// Each lane keeps up to U*NR independent 16-byte loads in flight before the FMA chain.  The loads of
-// the first chunk can be issued ahead of time (wave_prefetch), e.g. before the workgroup stages its
-// activation vector: weights never depend on activations.
-// ------------------------------------------------------------------------------------------------
-template <int NR, int U> struct Chunk {
-    u32x4 w[U][NR];
-};
-
-template <int NR, int U>
-__device__ __forceinline__ void chunk_load(Chunk<NR, U> &c, const uint16_t *const (&rows)[NR], int v0, int nvec) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int v = v0 + u * WAVE;
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            if (v < nvec) c.w[u][r] = ld_stream16(rows[r] + (size_t)v * 8);
-            else c.w[u][r] = u32x4{0u, 0u, 0u, 0u};
-        }
-    }
-}
-
-template <int DT, int NR, int U>
-__device__ __forceinline__ void chunk_fma(const Chunk<NR, U> &c, const float4 *xs, int v0, int nvec, float (&acc)[NR]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int v = v0 + u * WAVE;
-        if (v < nvec) {
-            const float4 a = xs[v], b = xs[nvec + v];
-#pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                float f[8];
-                unpack8<DT>(c.w[u][r], f);
-                float s = acc[r];
-                s = fmaf(f[0], a.x, s); s = fmaf(f[1], a.y, s); s = fmaf(f[2], a.z, s); s = fmaf(f[3], a.w, s);
-                s = fmaf(f[4], b.x, s); s = fmaf(f[5], b.y, s); s = fmaf(f[6], b.z, s); s = fmaf(f[7], b.w, s);
-                acc[r] = s;
-            }
-        }
-    }
-}
-
-// `pre` holds the chunk starting at v0 = lane if have_pre (in flight or arrived); it is clobbered.
-template <int DT, int NR, int U>
-__device__ __forceinline__ void wave_dots(const uint16_t *const (&rows)[NR], const float4 *xs, int nvec, int lane,
-                                          float (&out)[NR], Chunk<NR, U> &pre, bool have_pre) {
-    float acc[NR];
-#pragma unroll
-    for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-    for (int v0 = lane; v0 < nvec; v0 += WAVE * U) {  // one register buffer, reused for every chunk
-        if (!have_pre) chunk_load<NR, U>(pre, rows, v0, nvec);
-        have_pre = false;
-        chunk_fma<DT, NR, U>(pre, xs, v0, nvec, acc);
-    }
-#pragma unroll
-    for (int r = 0; r < NR; ++r) out[r] = wave_sum(acc[r]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -343,7 +285,7 @@ __global__ void k_fill_u16(uint16_t *p, size_t n, uint16_t v) {
 // Scores use a finite sentinel instead of -inf (Appendix B.3, item 3).
 // ------------------------------------------------------------------------------------------------
 constexpr float NEG_BIG = -1.0e30f;
-constexpr int ATTN_CHUNK_MIN = 64;
+constexpr int ATTN_CHUNK_MIN = 128;
 
 template <int KDT, int D, int GQ>
 __global__ void __launch_bounds__(256)
@@ -501,12 +443,15 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         ticket_s = __hip_atomic_fetch_add(&counters[kvh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_s != (uint32_t)(n_active - 1)) return;
-    // the last slice to arrive combines all slices of this KV head, in index order (reproducible)
+    // the last slice to arrive combines all slices of this KV head, in index order (reproducible).  One
+    // invalidate (L1 of this CU, non-coherent lines of this XCD's L2), then ordinary pipelined loads.
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();
     for (int idx = threadIdx.x; idx < GQ * n_active; idx += blockDim.x) {
         const int h = idx / n_active, t = idx - h * n_active;
         const float *rec = part + ((size_t)(kvh * GQ + h) * S + t) * PS;
-        sm[h][t] = __hip_atomic_load(rec + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sl[h][t] = __hip_atomic_load(rec + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm[h][t] = rec[0];
+        sl[h][t] = rec[1];
     }
     __syncthreads();
     for (int idx = threadIdx.x; idx < GQ * D; idx += blockDim.x) {
@@ -515,23 +460,11 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         float mt = NEG_BIG;
         for (int t = 0; t < n_active; ++t) mt = fmaxf(mt, sm[h][t]);
         float lt = 0.f, at = 0.f;
-        int t = 0;
-        for (; t + 4 <= n_active; t += 4) {
-            float a[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                a[u] = __hip_atomic_load(rec + (size_t)(t + u) * PS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float c = __expf(sm[h][t + u] - mt);
-                lt += sl[h][t + u] * c;
-                at += a[u] * c;
-            }
-        }
-        for (; t < n_active; ++t) {
+#pragma unroll 8
+        for (int t = 0; t < n_active; ++t) {
             const float c = __expf(sm[h][t] - mt);
             lt += sl[h][t] * c;
-            at += __hip_atomic_load(rec + (size_t)t * PS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * c;
+            at += rec[(size_t)t * PS] * c;
         }
         o[(size_t)(kvh * GQ + h) * D + i] = at / lt;
     }

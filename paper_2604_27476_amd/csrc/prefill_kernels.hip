@@ -116,19 +116,34 @@ __global__ void k_convert_w16(const uint16_t *__restrict__ src, uint16_t *__rest
 // global loads in flight during the MFMAs.
 // ------------------------------------------------------------------------------------------------
 constexpr int BM = 128, BN = 128, BK = 64, LDK = 72;
+constexpr int N_XCD = 8, GROUP_M = 8;
 
 template <int BDT, int EPI>
 __global__ void __launch_bounds__(256)
 k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
        int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
-       uint16_t *__restrict__ olo) {
+       uint16_t *__restrict__ olo, int n_mt, int n_nt) {
     __shared__ __attribute__((aligned(16))) uint16_t sAh[BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t sAl[BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM;
-    const int nb = blockIdx.x;  // n-tile index
+    // Tile order.  Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2;
+    // the workgroups that run together on one XCD are therefore given neighbouring tiles: XCD x owns a
+    // contiguous range of the virtual tile sequence, and that sequence walks GROUP_M row tiles for one
+    // column tile before moving to the next column tile, so a weight tile is fetched from HBM once and
+    // then served from L2 to the other row tiles.
+    int mt, nb;  // row tile, column tile
+    {
+        const int total = n_mt * n_nt, per_xcd = (total + N_XCD - 1) / N_XCD;
+        const int v = (int)(blockIdx.x % N_XCD) * per_xcd + (int)(blockIdx.x / N_XCD);
+        if (v >= total) return;
+        const int gsz = GROUP_M * n_nt, gid = v / gsz, first_m = gid * GROUP_M;
+        const int gm = min(GROUP_M, n_mt - first_m), r = v - gid * gsz;
+        mt = first_m + r % gm;
+        nb = r / gm;
+    }
+    const int m0 = mt * BM;
 
     // global source row of LDS row r of the B tile, or -1 if outside the matrix
     auto brow = [&](int r) -> int {
@@ -518,16 +533,15 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
                     const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, hipStream_t st) {
     const dim3 block(256);
     const int mt = (T + BM - 1) / BM;
-    if (epi == EPI_SWIGLU) {
-        const dim3 grid((N + 63) / 64, mt);
-        hipLaunchKernelGGL((k_gemm<BDT, EPI_SWIGLU>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo);
-    } else if (epi == EPI_RESID) {
-        const dim3 grid((N + BN - 1) / BN, mt);
-        hipLaunchKernelGGL((k_gemm<BDT, EPI_RESID>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo);
-    } else {
-        const dim3 grid((N + BN - 1) / BN, mt);
-        hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo);
-    }
+    const int nt = epi == EPI_SWIGLU ? (N + 63) / 64 : (N + BN - 1) / BN;
+    const int per_xcd = (mt * nt + N_XCD - 1) / N_XCD;
+    const dim3 grid(per_xcd * N_XCD);
+    if (epi == EPI_SWIGLU)
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_SWIGLU>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
+    else if (epi == EPI_RESID)
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_RESID>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
+    else
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
