@@ -126,9 +126,13 @@ def main() -> int:
     k_us = a.elapsed_time(b) * 1e3 / reps
     k_bytes = 2 * shape.intermediate * shape.hidden * 2 + shape.hidden * 4 + shape.hidden * 2 + shape.intermediate * 4
     k_gbps = k_bytes / (k_us * 1e-6) / 1e9
+    # HBM bytes per launch from the rocprofv3 --pmc runs summarised in
+    # profiles/decode_kernels_7b_ctx4096_pmc_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, both
+    # calibrated on a plain copy kernel); known for the 7B shape only
+    traffic = 271.87e6 + 0.077e6 if shape0.name == "qwen2.5-7b-shaped" else None
     roofline = {"kernel": "k_gateup (gate/up GEMV + RMSNorm prologue + SwiGLU epilogue)", "bound": "hbm",
                 "achieved": round(k_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": k_bytes, "us_per_launch": round(k_us, 2)}
 
     # ---- CPU oracle on this host: a few decode steps of the same model at the same context --------
