@@ -110,19 +110,26 @@ __global__ void k_convert_w16(const uint16_t *__restrict__ src, uint16_t *__rest
 
 // ------------------------------------------------------------------------------------------------
 // GEMM  C[T,N] = (A_hi + A_lo)[T,K] W16[N,K]^T / 2^8, every operand K-contiguous f16, so each MFMA operand
-// fragment is one 16-byte vector.  Workgroup tile 128 x 128 x 64, four waves in 2 x 2, each wave
-// 64 x 64 = 2 x 2 MFMA tiles; two MFMAs (hi, lo) per tile and k-step share the weight fragment.  Tiles
-// are staged through LDS (row stride 72 elements: conflict-free 128-bit reads) with the next tile's
-// global loads in flight during the MFMAs.
+// fragment is one 16-byte vector.  Four waves in 2 x 2; a wave owns TM x TN MFMA tiles of 32 x 32, i.e. the
+// workgroup tile is (64 TM) x (64 TN) x 64.  Per k-step a wave reads 2 TM + TN fragments from LDS for
+// 2 TM TN MFMAs (hi and lo share the weight fragment): the kernel is LDS-bandwidth bound, so the large
+// GEMMs use TM = 2, TN = 4 (0.5 reads per MFMA) and the small ones smaller tiles to keep >= 2 workgroups
+// per CU.  Tiles are staged through LDS (row stride 72 elements: conflict-free 128-bit reads) with the
+// next tile's global loads in flight during the MFMAs.
 // ------------------------------------------------------------------------------------------------
-constexpr int BM = 128, BN = 128, BK = 64, LDK = 72;
+constexpr int BK = 64, LDK = 72;
 constexpr int N_XCD = 8, GROUP_M = 8;
 
-template <int BDT, int EPI>
-__global__ void __launch_bounds__(256)
+template <int BDT, int EPI, int TM, int TN>
+__global__ void __launch_bounds__(256, 2)  // two workgroups per CU: at most 256 registers per lane
 k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
        int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
        uint16_t *__restrict__ olo, int n_mt, int n_nt) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int NA = BM * 8 / 256;  // 16-byte vectors of one A tile per thread
+    constexpr int NB = BN * 8 / 256;  // ... of the B tile
+    constexpr int WN = 32 * TN;       // columns per wave
+    static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "gate and up tiles are paired inside a wave");
     __shared__ __attribute__((aligned(16))) uint16_t sAh[BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t sAl[BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDK];
@@ -145,57 +152,68 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
     }
     const int m0 = mt * BM;
 
-    // global source row of LDS row r of the B tile, or -1 if outside the matrix
+    // Global source row of LDS row r of the B tile, or -1 if outside the matrix.  With the SwiGLU epilogue a
+    // wave's WN columns are WN/2 gate columns followed by the WN/2 up columns of the same neurons, so that
+    // gate and up of a neuron meet in one lane: the workgroup covers BN/2 neurons.
     auto brow = [&](int r) -> int {
         if constexpr (EPI == EPI_SWIGLU) {
-            const int j = nb * 64 + (r >> 6) * 32 + (r & 31);  // gate/up column
-            return j < N ? ((r >> 5) & 1) * N + j : -1;        // N = I; gate rows [0,I), up rows [I,2I)
+            const int w = r / WN, rr = r % WN, up = rr / (WN / 2), c = rr % (WN / 2);
+            const int j = nb * (BN / 2) + w * (WN / 2) + c;
+            return j < N ? up * N + j : -1;  // N = I; gate rows [0,I), up rows [I,2I)
         } else {
             const int n = nb * BN + r;
             return n < N ? n : -1;
         }
     };
 
-    // each thread moves 4 vectors of A_hi, A_lo and W per k-tile: vector id = tid + 256*i -> (row, kvec)
-    size_t oa[4], ob[4];
-    bool va[4], vb[4];
-    int so[4];
+    // vector id = tid + 256*i -> (row, kvec): 8 consecutive threads read 128 contiguous bytes of a row
+    uint32_t oa[NA], ob[NB];  // element offsets (every operand here has fewer than 2^31 elements)
+    bool va[NA], vb[NB];
+    int sa[NA], sb[NB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NA; ++i) {
         const int vid = tid + 256 * i, r = vid >> 3, kv = vid & 7;
         const int m = m0 + r;
         va[i] = m < T;
-        oa[i] = (size_t)(va[i] ? m : 0) * K + kv * 8;
+        oa[i] = (uint32_t)(va[i] ? m : 0) * (uint32_t)K + kv * 8;
+        sa[i] = r * LDK + kv * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int vid = tid + 256 * i, r = vid >> 3, kv = vid & 7;
         const int br = brow(r);
         vb[i] = br >= 0;
-        ob[i] = (size_t)(vb[i] ? br : 0) * K + kv * 8;
-        so[i] = r * LDK + kv * 8;
+        ob[i] = (uint32_t)(vb[i] ? br : 0) * (uint32_t)K + kv * 8;
+        sb[i] = r * LDK + kv * 8;
     }
-    u32x4 rah[4], ral[4], rb[4];
+    u32x4 rah[NA], ral[NA], rb[NB];
     const u32x4 zero = {0u, 0u, 0u, 0u};
+    const int kvo = (tid & 7) * 8;
     auto gload = [&](int k0) {
+        const bool kin = k0 + kvo < K;  // K is a multiple of 8
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const bool kin = k0 + ((tid + 256 * i) & 7) * 8 < K;
+        for (int i = 0; i < NA; ++i) {
             rah[i] = (va[i] && kin) ? ld16(Ahi + oa[i] + k0) : zero;
             ral[i] = (va[i] && kin) ? ld16(Alo + oa[i] + k0) : zero;
-            rb[i] = (vb[i] && kin) ? ld16(W + ob[i] + k0) : zero;
         }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) rb[i] = (vb[i] && kin) ? ld16(W + ob[i] + k0) : zero;
     };
     auto sstore = [&]() {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<u32x4 *>(sAh + so[i]) = rah[i];
-            *reinterpret_cast<u32x4 *>(sAl + so[i]) = ral[i];
-            *reinterpret_cast<u32x4 *>(sB + so[i]) = rb[i];
+        for (int i = 0; i < NA; ++i) {
+            *reinterpret_cast<u32x4 *>(sAh + sa[i]) = rah[i];
+            *reinterpret_cast<u32x4 *>(sAl + sa[i]) = ral[i];
         }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<u32x4 *>(sB + sb[i]) = rb[i];
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
@@ -208,21 +226,24 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
         if (kt + 1 < nk) gload((kt + 1) * BK);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            u32x4 fah[2], fal[2], fb[2];
+            u32x4 fah[TM], fal[TM], fb[TN];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int ao = (wm * 64 + t * 32 + fr) * LDK + ks * 16 + fk;
+            for (int t = 0; t < TM; ++t) {
+                const int ao = (wm * 32 * TM + t * 32 + fr) * LDK + ks * 16 + fk;
                 fah[t] = *reinterpret_cast<const u32x4 *>(sAh + ao);
                 fal[t] = *reinterpret_cast<const u32x4 *>(sAl + ao);
-                fb[t] = *reinterpret_cast<const u32x4 *>(sB + (wn * 64 + t * 32 + fr) * LDK + ks * 16 + fk);
             }
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int t = 0; t < TN; ++t)
+                fb[t] = *reinterpret_cast<const u32x4 *>(sB + (wn * WN + t * 32 + fr) * LDK + ks * 16 + fk);
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    acc[a][b] = mfma32<DT_F16>(fah[a], fb[b], acc[a][b]);
-                    acc[a][b] = mfma32<DT_F16>(fal[a], fb[b], acc[a][b]);
-                }
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(fah[a], fb[b], acc[a][b]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(fal[a], fb[b], acc[a][b]);
         }
         __syncthreads();
         if (kt + 1 < nk) {
@@ -231,28 +252,31 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
         }
     }
 
-    // epilogue: slot i of tile (a, b) is row wm*64 + a*32 + 8*(i/4) + 4*(lane/32) + i%4, column lane%32
+    // epilogue: slot i of tile (a, b) is row wm*32*TM + a*32 + 8*(i/4) + 4*(lane/32) + i%4, column lane%32
     const int hf = lane >> 5;
     constexpr float UNSCALE = 1.0f / W16_SCALE;
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int a = 0; a < TM; ++a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int m = m0 + wm * 64 + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+            const int m = m0 + wm * 32 * TM + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
             if (m >= T) continue;
             if constexpr (EPI == EPI_SWIGLU) {
-                const int j = nb * 64 + wn * 32 + fr;
-                if (j < N) {
-                    const float g = acc[a][0][i] * UNSCALE, u = acc[a][1][i] * UNSCALE;
-                    uint16_t h, l;
-                    split_f16(g / (1.0f + expf(-g)) * u, h, l);
-                    ohi[(size_t)m * N + j] = h;
-                    olo[(size_t)m * N + j] = l;
+#pragma unroll
+                for (int b = 0; b < TN / 2; ++b) {
+                    const int j = nb * (BN / 2) + wn * (WN / 2) + b * 32 + fr;
+                    if (j < N) {
+                        const float g = acc[a][b][i] * UNSCALE, u = acc[a][b + TN / 2][i] * UNSCALE;
+                        uint16_t h, l;
+                        split_f16(g / (1.0f + expf(-g)) * u, h, l);
+                        ohi[(size_t)m * N + j] = h;
+                        olo[(size_t)m * N + j] = l;
+                    }
                 }
             } else {
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const int n = nb * BN + wn * 64 + b * 32 + fr;
+                for (int b = 0; b < TN; ++b) {
+                    const int n = nb * BN + wn * WN + b * 32 + fr;
                     if (n < N) {
                         const float c = acc[a][b][i] * UNSCALE;
                         if constexpr (EPI == EPI_RESID) outf[(size_t)m * N + n] += c;
@@ -528,20 +552,34 @@ void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, size_
         hipLaunchKernelGGL(k_convert_w16<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, nvec);
 }
 
-template <int BDT>
-static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
-                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, hipStream_t st) {
+template <int BDT, int TM, int TN>
+static void gemm_tile(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                      const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, hipStream_t st) {
     const dim3 block(256);
-    const int mt = (T + BM - 1) / BM;
-    const int nt = epi == EPI_SWIGLU ? (N + 63) / 64 : (N + BN - 1) / BN;
+    const int mt = (T + 64 * TM - 1) / (64 * TM);
+    const int ncol = epi == EPI_SWIGLU ? 32 * TN : 64 * TN;  // output columns (neurons) per workgroup
+    const int nt = (N + ncol - 1) / ncol;
     const int per_xcd = (mt * nt + N_XCD - 1) / N_XCD;
     const dim3 grid(per_xcd * N_XCD);
     if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((k_gemm<BDT, EPI_SWIGLU>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_SWIGLU, TM, TN>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
     else if (epi == EPI_RESID)
-        hipLaunchKernelGGL((k_gemm<BDT, EPI_RESID>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_RESID, TM, TN>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
     else
-        hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
+        hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32, TM, TN>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
+}
+
+template <int BDT>
+static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, hipStream_t st) {
+    // largest tile that still gives every one of the 256 CUs two workgroups
+    auto count = [&](int tm, int tn) {
+        const int ncol = epi == EPI_SWIGLU ? 32 * tn : 64 * tn;
+        return ((T + 64 * tm - 1) / (64 * tm)) * ((N + ncol - 1) / ncol);
+    };
+    if (count(2, 4) >= 512) gemm_tile<BDT, 2, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, st);
+    else if (count(2, 2) >= 512) gemm_tile<BDT, 2, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, st);
+    else gemm_tile<BDT, 1, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, st);
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
