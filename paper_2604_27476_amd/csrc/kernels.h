@@ -106,8 +106,11 @@ enum GemmEpi { EPI_BIAS_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 // C = (A_hi + A_lo)[T,K] W16[N,K]^T / 2^8 with an epilogue:
 //   EPI_BIAS_F32: out_f32[T,N] = C + bias      EPI_RESID: X[T,N] += C
 //   EPI_SWIGLU  : W16 is [2 I, K] (gate | up), out_hi + out_lo [T,I] = silu(C_gate) * C_up, N = I
+// ws: GEMM_WS_BYTES of scratch for the k-slices of split tiles (null: tiles are never split)
+constexpr size_t GEMM_WS_BYTES = (size_t)64 << 20;
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
-                 int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, hipStream_t st);
+                 int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
+                 hipStream_t st);
 // RoPE + cache write for positions p0..p0+T-1; sum_s Qs[s][t] = RoPE(q_t)
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
                     uint16_t *Qs, size_t q_stride, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);

@@ -29,7 +29,7 @@ struct Layout {
     size_t x, q, o, h, part, counters, logits, hidden, part_val, part_idx, ints;
     size_t qkv_raw, layer_table, sync, trace;  // fused decode step
     // prefill scratch
-    size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Vt, tok;
+    size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Vt, tok, gemm_ws;
     size_t total;
 };
 
@@ -122,6 +122,7 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.Hlo = take(Tm * I * 2);
     L.Vt = take(kvd * ctx_pad * 2);
     L.tok = take(Tm * 4);
+    L.gemm_ws = take(GEMM_WS_BYTES);
     L.total = off;
 }
 
@@ -442,6 +443,7 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
              *Hlo = m->at<uint16_t>(m->L.Hlo), *Vt = m->at<uint16_t>(m->L.Vt);
     const size_t q_stride = (size_t)D.max_seq * D.qd();
     const float *rc = m->at<float>(m->L.rope_cos), *rs = m->at<float>(m->L.rope_sin);
+    float *ws = m->at<float>(m->L.gemm_ws);
     launch_embed_rows(D, m->at<uint16_t>(m->L.embed), static_cast<const uint16_t *>(embeds_dev), (int)n_embeds, tok,
                       (int)n_tokens, X, st);
     for (int l = 0; l < D.L; ++l) {
@@ -449,14 +451,22 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
         const edgefm_model::PrefillW &P = m->PW[l];
         launch_rmsnorm_rows(D, X, W.attn_norm, T, Ahi, Alo, st);
         launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, D.qkv_bias ? W.bqkv : nullptr, QKV, nullptr,
-                    nullptr, st);
+                    nullptr, ws, st);
         launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, m->kc(l), m->vc(l), st);
         launch_transpose_v(D, m->vc(l), ctx, ctx_pad, Vt, st);
         launch_flash_attn(D, Qs, q_stride, m->kc(l), Vt, ctx_pad, T, p0, Ohi, Olo, st);
-        launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, st);
+        launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, st);
+        if (l == D.L - 1) {
+            // Nothing reads the last layer's MLP output except the final norm of the last position (the
+            // cache rows of every layer are complete at this point): one row through the decode kernels.
+            float *xl = X + (size_t)(T - 1) * D.H, *h = m->at<float>(m->L.h);
+            launch_gateup(D, m->G, W, xl, h, st);
+            launch_gemv_resid(D, m->G, W.w_down, D.I, h, xl, st);
+            break;
+        }
         launch_rmsnorm_rows(D, X, W.mlp_norm, T, Ahi, Alo, st);
-        launch_gemm(D, EPI_SWIGLU, Ahi, Alo, P.w_gate_up, T, D.I, D.H, nullptr, nullptr, Hhi, Hlo, st);
-        launch_gemm(D, EPI_RESID, Hhi, Hlo, P.w_down, T, D.H, D.I, nullptr, X, nullptr, nullptr, st);
+        launch_gemm(D, EPI_SWIGLU, Ahi, Alo, P.w_gate_up, T, D.I, D.H, nullptr, nullptr, Hhi, Hlo, ws, st);
+        launch_gemm(D, EPI_RESID, Hhi, Hlo, P.w_down, T, D.H, D.I, nullptr, X, nullptr, nullptr, ws, st);
     }
     // only the last position needs logits: final norm + lm_head as a GEMV on that row
     launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), X + (size_t)(T - 1) * D.H,

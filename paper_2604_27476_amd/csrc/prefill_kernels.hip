@@ -12,6 +12,9 @@
 //               magnitude >= 2^-25), two MFMAs per product;
 //   attention:  q and p as three bf16 terms (24 bits) against the bf16 cache, or two f16 terms against an
 //               f16 cache: the cache operands are used exactly as stored.
+#include <stdlib.h>
+
+#include <algorithm>
 #include "common.h"
 #include "kernels.h"
 
@@ -283,6 +286,310 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
                         else outf[(size_t)m * N + n] = c + (bias ? up1<BDT>(bias[n]) : 0.f);
                     }
                 }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Pipelined GEMM (same contract as k_gemm; K must be a multiple of 32): 256 x 256 x 32 workgroup tile,
+// eight waves in 4 x 2, each wave 64 x 128 (TM = 2, TN = 4: 0.5 LDS fragment reads per MFMA).  The three
+// operand tiles go from global memory straight into LDS (global_load_lds, no staging registers, no
+// ds_write) through a ring of three stages, two to three k-tiles ahead of the MFMAs, with one barrier per
+// k-tile.  LDS rows are 64 bytes (4 chunks of 16 B); chunk c of row r sits in slot c ^ ((r >> 1) & 3),
+// which makes both the 1 KB wave-wide DMA writes and the 128-bit fragment reads conflict-free.
+// Rows beyond T or N are clamped to the last valid row (their products are never stored).
+// ------------------------------------------------------------------------------------------------
+constexpr int PK = 32;                     // k-tile depth
+constexpr int P_STAGES = 3;
+constexpr int P_BM = 256, P_BN = 256;
+constexpr int P_STAGE_ELEMS = (2 * P_BM + P_BN) * PK;  // A_hi | A_lo | B, f16 elements per stage (48 KB)
+constexpr int PIPE_MAX_SPLITS = 8;          // k-slices per tile at most
+constexpr int PIPE_MIN_SLICE_TILES = 16;    // k-tiles per slice at least (keeps the tile prologue and epilogue small)
+static_assert((size_t)P_BM * P_BN * 4 * 256 <= GEMM_WS_BYTES, "a split round (slices x tiles <= CUs) has to fit the workspace");
+
+// Which tiles a launch covers: tiles [tile_begin, tile_begin + n_tiles) of the n_mt x n_nt grid in grouped
+// order, each cut into k_splits slices along K.  With k_splits > 1 every slice leaves its partial tile in
+// ws[(slice * n_tiles + local tile)][256][256] and k_splitk_finish adds the slices up in a fixed order.
+struct PipeRange {
+    int n_mt, n_nt, tile_begin, n_tiles, k_splits;
+    float *ws;
+};
+__device__ __forceinline__ void pipe_tile(const PipeRange &R, int tl, int &mt, int &nb) {
+    const int v = R.tile_begin + tl;
+    const int gsz = GROUP_M * R.n_nt, gid = v / gsz, first_m = gid * GROUP_M;
+    const int gm = min(GROUP_M, R.n_mt - first_m), r = v - gid * gsz;
+    mt = first_m + r % gm;
+    nb = r / gm;
+}
+
+// One LDS-DMA instruction: lane l copies the 16 bytes at base + voff (bytes) to LDS address lds + 16 l.
+// Written as inline assembly on purpose: the compiler books its own LDS-DMA builtin as a flat access that
+// is pending on both memory counters, and while one is in flight (always, in a prefetching loop) it drains
+// the LDS counter to zero before every use of a fragment, which serialises LDS reads and MFMAs.  The
+// transfer is tracked by vmcnt; the callers wait on it explicitly.
+__device__ __forceinline__ void lds_dma16(const uint16_t *base, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));
+}
+
+template <int BDT, int EPI>
+__global__ void __launch_bounds__(512)
+k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
+            int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
+            uint16_t *__restrict__ olo, PipeRange R) {
+    constexpr int TM = 2, TN = 4, WN = 32 * TN;
+    extern __shared__ __attribute__((aligned(1024))) uint16_t ring[];  // P_STAGES x (A_hi, A_lo, B)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    // work unit = (k-slice, tile); consecutive units go to one XCD, slice-major, so that the workgroups
+    // sharing an L2 walk the same k-range of neighbouring tiles
+    const int units = R.n_tiles * R.k_splits, per_xcd = (units + N_XCD - 1) / N_XCD;
+    const int unit = (int)(blockIdx.x % N_XCD) * per_xcd + (int)(blockIdx.x / N_XCD);
+    if (unit >= units) return;
+    const int split = unit / R.n_tiles, tl = unit - split * R.n_tiles;
+    int mt, nb;
+    pipe_tile(R, tl, mt, nb);
+    const int m0 = mt * P_BM;
+    int nk;  // k-tiles of this slice
+    {
+        const int nk_all = K / PK;
+        const int kbeg = (int)((long long)split * nk_all / R.k_splits);
+        nk = (int)((long long)(split + 1) * nk_all / R.k_splits) - kbeg;
+        Ahi += (size_t)kbeg * PK;
+        Alo += (size_t)kbeg * PK;
+        W += (size_t)kbeg * PK;
+    }
+    auto brow = [&](int r) -> int {  // global weight row of B-tile row r (clamped inside the matrix)
+        if constexpr (EPI == EPI_SWIGLU) {
+            const int w = r / WN, rr = r % WN, up = rr / (WN / 2), c = rr % (WN / 2);
+            const int j = min(nb * (P_BN / 2) + w * (WN / 2) + c, N - 1);
+            return up * N + j;
+        } else {
+            return min(nb * P_BN + r, N - 1);
+        }
+    };
+    // DMA plan: one instruction moves 16 rows x 64 B.  Wave w issues, per stage, instructions 2w and 2w+1 of
+    // each of the three tiles (rows 32w .. 32w+31).  Lane l of an instruction covers row R0 + l/4, slot l%4,
+    // i.e. logical chunk (l%4) ^ ((row >> 1) & 3).
+    uint32_t ga[2], gb[2];  // byte offsets of this lane's chunk at k0 = 0 (A_hi and A_lo share ga)
+    int lrow[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = 32 * wave + 16 * i + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 1) & 3);
+        ga[i] = ((uint32_t)min(m0 + r, T - 1) * (uint32_t)K + c * 8) * 2u;
+        gb[i] = ((uint32_t)brow(r) * (uint32_t)K + c * 8) * 2u;
+        lrow[i] = (32 * wave + 16 * i) * PK * 2;  // LDS byte offset of the instruction's first row
+    }
+    auto issue = [&](int kt) {
+        const uint32_t st = lds_addr(ring) + (kt % P_STAGES) * (P_STAGE_ELEMS * 2);
+        const int k0 = kt * PK;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            lds_dma16(Ahi + k0, ga[i], st + lrow[i]);
+            lds_dma16(Alo + k0, ga[i], st + P_BM * PK * 2 + lrow[i]);
+            lds_dma16(W + k0, gb[i], st + 2 * P_BM * PK * 2 + lrow[i]);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int fr = lane & 31, hf = lane >> 5;
+    // Fragment registers of one 16-deep k-step: A_hi, A_lo (TM each) and B (TN).
+    struct Frag {
+        u32x4 ah[TM], al[TM], b[TN];
+    };
+    auto read_frag = [&](Frag &f, int kt, int ks) {
+        const uint16_t *st = ring + (kt % P_STAGES) * P_STAGE_ELEMS;
+#pragma unroll
+        for (int t = 0; t < TM; ++t) {
+            const int r = wm * 64 + t * 32 + fr;
+            const int off = r * PK + (((ks * 2 + hf) ^ ((r >> 1) & 3)) << 3);
+            f.ah[t] = *reinterpret_cast<const u32x4 *>(st + off);
+            f.al[t] = *reinterpret_cast<const u32x4 *>(st + P_BM * PK + off);
+        }
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            const int r = wn * WN + t * 32 + fr;
+            f.b[t] = *reinterpret_cast<const u32x4 *>(st + 2 * P_BM * PK + r * PK +
+                                                      (((ks * 2 + hf) ^ ((r >> 1) & 3)) << 3));
+        }
+    };
+    auto mfma_frag = [&](const Frag &f) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(f.ah[a], f.b[b], acc[a][b]);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(f.al[a], f.b[b], acc[a][b]);
+    };
+    static_assert(PK == 32 && P_STAGES == 3, "the schedule below is written for two k-steps per tile and a ring of three");
+    // Schedule: the eight waves form two groups of four (one wave of each group per SIMD) that alternate
+    // between a memory phase (LDS-DMA issue, fragment reads of a whole k-tile) and a compute phase (the 32
+    // MFMAs of that k-tile).  The groups run one phase apart, so in every phase each SIMD has one wave that
+    // multiplies while the other one reads: the matrix pipe never waits for LDS, and one barrier per phase
+    // hands the roles over.  Phase q ends with barrier q; group 0 reads tile kt in phase 2kt and multiplies in
+    // phase 2kt+1, group 1 reads it in phase 2kt+1 and multiplies in phase 2kt+2.  Only the reading group issues
+    // LDS-DMA (an issue costs its wave about 16 cycles per KB moved, which would otherwise delay MFMAs): each
+    // wave loads its share of tile kt+2 at the start of the phase in which it reads tile kt.  The stage that
+    // receives it held tile kt-1, which both groups finished reading before barrier 2kt-1; every share of
+    // tile kt+2 has landed before barrier 2kt+3.
+    const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);
+    Frag f0, f1;
+    issue(0);
+    if (nk > 1) issue(1);
+    if (nk > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (grp == 0) {
+        for (int kt = 0; kt < nk; ++kt) {
+            if (kt + 2 < nk) issue(kt + 2);
+            read_frag(f0, kt, 0);
+            read_frag(f1, kt, 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();  // barrier 2kt
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_frag(f0);
+            mfma_frag(f1);
+            __builtin_amdgcn_sched_barrier(0);
+            // this wave's share of tile kt+1 has landed; only tile kt+2 may still be in flight
+            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();  // barrier 2kt+1
+            asm volatile("" ::: "memory");
+        }
+    } else {
+        __builtin_amdgcn_s_barrier();  // barrier 0
+        asm volatile("" ::: "memory");
+        for (int kt = 0; kt < nk; ++kt) {
+            if (kt + 2 < nk) issue(kt + 2);
+            read_frag(f0, kt, 0);
+            read_frag(f1, kt, 1);
+            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();  // barrier 2kt+1
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_frag(f0);
+            mfma_frag(f1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 1 < nk) {
+                __builtin_amdgcn_s_barrier();  // barrier 2kt+2 (the last phase has no successor)
+                asm volatile("" ::: "memory");
+            }
+        }
+    }
+
+    constexpr float UNSCALE = 1.0f / W16_SCALE;
+    if (R.k_splits > 1) {  // partial sums of this k-slice, tile-local [256][256] fp32
+        float *wt = R.ws + (size_t)(split * R.n_tiles + tl) * (P_BM * P_BN);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = wm * 64 + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+#pragma unroll
+                for (int b = 0; b < TN; ++b) wt[row * P_BN + wn * WN + b * 32 + fr] = acc[a][b][i] * UNSCALE;
+            }
+        return;
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wm * 64 + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+            if (m >= T) continue;
+            if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int b = 0; b < TN / 2; ++b) {
+                    const int j = nb * (P_BN / 2) + wn * (WN / 2) + b * 32 + fr;
+                    if (j < N) {
+                        const float g = acc[a][b][i] * UNSCALE, u = acc[a][b + TN / 2][i] * UNSCALE;
+                        uint16_t h, l;
+                        split_f16(g / (1.0f + expf(-g)) * u, h, l);
+                        ohi[(size_t)m * N + j] = h;
+                        olo[(size_t)m * N + j] = l;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const int n = nb * P_BN + wn * WN + b * 32 + fr;
+                    if (n < N) {
+                        const float c = acc[a][b][i] * UNSCALE;
+                        if constexpr (EPI == EPI_RESID) outf[(size_t)m * N + n] += c;
+                        else outf[(size_t)m * N + n] = c + (bias ? up1<BDT>(bias[n]) : 0.f);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Sum of the k-slices of a split launch plus the epilogue of k_gemm_pipe.  Grid (tiles, 256 / FIN_ROWS): one
+// workgroup per FIN_ROWS rows of a tile, four adjacent outputs per thread (128-bit loads, all of a thread's
+// loads in flight together).  The slices are added in slice order, so the result does not depend on timing.
+constexpr int FIN_ROWS = 16;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <int BDT, int EPI>
+__global__ void __launch_bounds__(256)
+k_splitk_finish(PipeRange R, int T, int N, const uint16_t *__restrict__ bias, float *__restrict__ outf,
+                uint16_t *__restrict__ ohi, uint16_t *__restrict__ olo) {
+    constexpr int NOUT = EPI == EPI_SWIGLU ? P_BN / 2 : P_BN;  // outputs per tile row
+    constexpr int TPR = NOUT / 4, RPI = 256 / TPR;             // threads per row, rows per pass
+    const int tl = blockIdx.x;
+    int mt, nb;
+    pipe_tile(R, tl, mt, nb);
+    const size_t slice = (size_t)R.n_tiles * (P_BM * P_BN);
+    const float *wt = R.ws + (size_t)tl * (P_BM * P_BN);
+    const int o = (threadIdx.x % TPR) * 4;
+#pragma unroll
+    for (int pass = 0; pass < FIN_ROWS / RPI; ++pass) {
+        const int row = blockIdx.y * FIN_ROWS + pass * RPI + threadIdx.x / TPR;
+        const int m = mt * P_BM + row;
+        if (m >= T) continue;
+        if constexpr (EPI == EPI_SWIGLU) {
+            const int j = nb * NOUT + o;
+            const int gc = (o >> 6) * 128 + (o & 63);  // gate column of the tile; its up column is 64 further
+            f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = g;
+            for (int sl = 0; sl < R.k_splits; ++sl) {
+                g += *reinterpret_cast<const f32x4 *>(wt + sl * slice + row * P_BN + gc);
+                u += *reinterpret_cast<const f32x4 *>(wt + sl * slice + row * P_BN + gc + 64);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (j + e >= N) continue;
+                uint16_t h, l;
+                split_f16(g[e] / (1.0f + expf(-g[e])) * u[e], h, l);
+                ohi[(size_t)m * N + j + e] = h;
+                olo[(size_t)m * N + j + e] = l;
+            }
+        } else {
+            const int n = nb * NOUT + o;
+            f32x4 c = {0.f, 0.f, 0.f, 0.f};
+            for (int sl = 0; sl < R.k_splits; ++sl) c += *reinterpret_cast<const f32x4 *>(wt + sl * slice + row * P_BN + o);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (n + e >= N) continue;
+                if constexpr (EPI == EPI_RESID) outf[(size_t)m * N + n + e] += c[e];
+                else outf[(size_t)m * N + n + e] = c[e] + (bias ? up1<BDT>(bias[n + e]) : 0.f);
             }
         }
     }
@@ -569,9 +876,84 @@ static void gemm_tile(int epi, const uint16_t *Ahi, const uint16_t *Alo, const u
         hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32, TM, TN>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
 }
 
+// The pipelined kernel needs 144 KB of dynamic LDS: raise the ceiling once; EDGEFM_GEMM=tile disables it.
+static bool gemm_pipe_enabled() {
+    static int state = -1;
+    if (state < 0) {
+        const char *e = getenv("EDGEFM_GEMM");
+        bool ok = !(e && e[0] == 't');
+        const int lds = P_STAGES * P_STAGE_ELEMS * 2;
+#define PIPE_ATTR(K) ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
+        PIPE_ATTR((k_gemm_pipe<DT_BF16, EPI_SWIGLU>)) PIPE_ATTR((k_gemm_pipe<DT_BF16, EPI_RESID>))
+        PIPE_ATTR((k_gemm_pipe<DT_BF16, EPI_BIAS_F32>)) PIPE_ATTR((k_gemm_pipe<DT_F16, EPI_SWIGLU>))
+        PIPE_ATTR((k_gemm_pipe<DT_F16, EPI_RESID>)) PIPE_ATTR((k_gemm_pipe<DT_F16, EPI_BIAS_F32>))
+#undef PIPE_ATTR
+        state = ok ? 1 : 0;
+    }
+    return state == 1;
+}
+
+static int device_cu_count() {
+    static int n = 0;
+    if (!n) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        n = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) ? prop.multiProcessorCount : 256;
+    }
+    return n;
+}
+
+template <int BDT>
+static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                        const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
+                        hipStream_t st) {
+    const int per_xcd = (R.n_tiles * R.k_splits + N_XCD - 1) / N_XCD;
+    const dim3 grid(per_xcd * N_XCD), block(512);
+    const size_t lds = (size_t)P_STAGES * P_STAGE_ELEMS * 2;
+    if (epi == EPI_SWIGLU)
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+    else if (epi == EPI_RESID)
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+    else
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+    if (R.k_splits > 1) {
+        const dim3 fgrid(R.n_tiles, P_BM / FIN_ROWS);
+        if (epi == EPI_SWIGLU)
+            hipLaunchKernelGGL((k_splitk_finish<BDT, EPI_SWIGLU>), fgrid, dim3(256), 0, st, R, T, N, bias, outf, ohi, olo);
+        else if (epi == EPI_RESID)
+            hipLaunchKernelGGL((k_splitk_finish<BDT, EPI_RESID>), fgrid, dim3(256), 0, st, R, T, N, bias, outf, ohi, olo);
+        else
+            hipLaunchKernelGGL((k_splitk_finish<BDT, EPI_BIAS_F32>), fgrid, dim3(256), 0, st, R, T, N, bias, outf, ohi, olo);
+    }
+}
+
 template <int BDT>
 static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
-                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, hipStream_t st) {
+                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, hipStream_t st) {
+    const int pipe_mt = (T + P_BM - 1) / P_BM;
+    const int pipe_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
+    const size_t w_rows = epi == EPI_SWIGLU ? 2 * (size_t)N : (size_t)N;
+    const bool fits32 = std::max((size_t)T, w_rows) * (size_t)K * 2 < ((size_t)1 << 32);  // 32-bit byte offsets
+    // Pipelined kernel (one 256 x 256 tile per CU at a time) for prompts long enough to fill its row tiles.
+    // Tiles that would start a partly filled last round are cut along K instead, so that the round is short
+    // and busy on every CU; their slices meet in the workspace.
+    if (T >= 2 * P_BM && K % PK == 0 && fits32 && gemm_pipe_enabled()) {
+        const int n_cu = std::min(device_cu_count(), 256), tiles = pipe_mt * pipe_nt, nk = K / PK;
+        const int rem = tiles % n_cu, full = tiles - rem;
+        int splits = 1;
+        if (rem > 0 && ws) splits = std::min(std::min(n_cu / rem, PIPE_MAX_SPLITS), nk / PIPE_MIN_SLICE_TILES);
+        if (splits < 2) {
+            if (tiles * 4 >= n_cu * 3) {  // at least three quarters of the CUs busy in the (only) partial round
+                pipe_launch<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{pipe_mt, pipe_nt, 0, tiles, 1, nullptr}, st);
+                return;
+            }
+        } else {
+            if (full > 0)
+                pipe_launch<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{pipe_mt, pipe_nt, 0, full, 1, nullptr}, st);
+            pipe_launch<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{pipe_mt, pipe_nt, full, rem, splits, ws}, st);
+            return;
+        }
+    }
     // largest tile that still gives every one of the 256 CUs two workgroups
     auto count = [&](int tm, int tn) {
         const int ncol = epi == EPI_SWIGLU ? 32 * tn : 64 * tn;
@@ -583,9 +965,10 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
-                 int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, hipStream_t st) {
-    if (D.wdt == DT_BF16) gemm_dt<DT_BF16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, st);
-    else gemm_dt<DT_F16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, st);
+                 int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
+                 hipStream_t st) {
+    if (D.wdt == DT_BF16) gemm_dt<DT_BF16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, st);
+    else gemm_dt<DT_F16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, st);
 }
 
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
