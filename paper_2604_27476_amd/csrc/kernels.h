@@ -91,9 +91,8 @@ void mega_build_stages(const Dims &D, const LayerW *lw, const MegaArgs &a, MegaS
 hipError_t launch_decode_mega(const Dims &D, const Geo &G, const MegaArgs &args, hipStream_t st);
 
 // ------------------------------------------------------------------ prefill (m = T)
-// Activations reach the matrix cores as a sum of 16-bit terms (see prefill_kernels.hip): GEMM A operands are
-// f16 pairs (hi, lo); the rotated query is NS terms of the cache dtype (3 for bf16, 2 for f16), term s at
-// Qs + s * q_stride.
+// Activations reach the matrix cores as a sum of two f16 terms (see prefill_kernels.hip): GEMM A operands are
+// pairs (hi, lo); so is the rotated query, term s at Qs + s * q_stride.
 // X[t] <- upcast(embeds[t]) for t < n_embeds, upcast(E[tok[t - n_embeds]]) after
 void launch_embed_rows(const Dims &D, const uint16_t *embed, const uint16_t *embeds, int n_embeds, const int *tok,
                        int n_tokens, float *X, hipStream_t st);
@@ -111,13 +110,15 @@ constexpr size_t GEMM_WS_BYTES = (size_t)64 << 20;
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
                  int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
                  hipStream_t st);
-// RoPE + cache write for positions p0..p0+T-1; sum_s Qs[s][t] = RoPE(q_t)
+// RoPE + cache write for positions p0..p0+T-1; Qs[0][t] + Qs[1][t] = RoPE(q_t)
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
                     uint16_t *Qs, size_t q_stride, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);
-// Vt[kvh][i][j] <- V[l][kvh][j][i] for j < ctx (row stride ctx_pad)
-void launch_transpose_v(const Dims &D, const uint16_t *vcache_l, int ctx, int ctx_pad, uint16_t *Vt, hipStream_t st);
+// f16 attention operands of one layer for context rows j < ctx (zero up to ctx_pad, a multiple of 64):
+// Kf[kvh][j][i] <- K[l][kvh][j][i];  Vt[kvh][i][.] <- V[l][kvh][j][i], keys permuted within groups of 16
+void launch_prep_kv(const Dims &D, const uint16_t *kcache_l, const uint16_t *vcache_l, int ctx, int ctx_pad,
+                    uint16_t *Kf, uint16_t *Vt, hipStream_t st);
 // causal GQA flash attention for queries p0..p0+T-1 over keys 0..p0+t; output as an f16 pair
-void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *kcache_l, const uint16_t *Vt,
+void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *Kf, const uint16_t *Vt,
                        int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st);
 
 }  // namespace efm

@@ -29,7 +29,7 @@ struct Layout {
     size_t x, q, o, h, part, counters, logits, hidden, part_val, part_idx, ints;
     size_t qkv_raw, layer_table, sync, trace;  // fused decode step
     // prefill scratch
-    size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Vt, tok, gemm_ws;
+    size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Kf, Vt, tok, gemm_ws;
     size_t total;
 };
 
@@ -115,11 +115,12 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.Ahi = take(Tm * H * 2);
     L.Alo = take(Tm * H * 2);
     L.QKV = take(Tm * R * 4);
-    L.Qs = take(3 * Tm * qd * 2);
+    L.Qs = take(2 * Tm * qd * 2);
     L.Ohi = take(Tm * qd * 2);
     L.Olo = take(Tm * qd * 2);
     L.Hhi = take(Tm * I * 2);
     L.Hlo = take(Tm * I * 2);
+    L.Kf = take(kvd * ctx_pad * 2);
     L.Vt = take(kvd * ctx_pad * 2);
     L.tok = take(Tm * 4);
     L.gemm_ws = take(GEMM_WS_BYTES);
@@ -440,7 +441,7 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     float *X = m->at<float>(m->L.X), *QKV = m->at<float>(m->L.QKV);
     uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo), *Qs = m->at<uint16_t>(m->L.Qs),
              *Ohi = m->at<uint16_t>(m->L.Ohi), *Olo = m->at<uint16_t>(m->L.Olo), *Hhi = m->at<uint16_t>(m->L.Hhi),
-             *Hlo = m->at<uint16_t>(m->L.Hlo), *Vt = m->at<uint16_t>(m->L.Vt);
+             *Hlo = m->at<uint16_t>(m->L.Hlo), *Kf = m->at<uint16_t>(m->L.Kf), *Vt = m->at<uint16_t>(m->L.Vt);
     const size_t q_stride = (size_t)D.max_seq * D.qd();
     const float *rc = m->at<float>(m->L.rope_cos), *rs = m->at<float>(m->L.rope_sin);
     float *ws = m->at<float>(m->L.gemm_ws);
@@ -453,8 +454,8 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
         launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, D.qkv_bias ? W.bqkv : nullptr, QKV, nullptr,
                     nullptr, ws, st);
         launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, m->kc(l), m->vc(l), st);
-        launch_transpose_v(D, m->vc(l), ctx, ctx_pad, Vt, st);
-        launch_flash_attn(D, Qs, q_stride, m->kc(l), Vt, ctx_pad, T, p0, Ohi, Olo, st);
+        launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
+        launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, st);
         launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, st);
         if (l == D.L - 1) {
             // Nothing reads the last layer's MLP output except the final norm of the last position (the

@@ -597,25 +597,13 @@ k_splitk_finish(PipeRange R, int T, int N, const uint16_t *__restrict__ bias, fl
 
 // ------------------------------------------------------------------------------------------------
 // RoPE (rotate-half pairing, Appendix B.3) + KV-cache write for T new positions starting at p0.
-// One thread per (t, head, i < d/2).  The rotated query is stored as NS terms of the cache dtype
-// (q = q_1 + ... + q_NS), the MFMA partner format of the cached K.
+// One thread per (t, head, i < d/2).  The rotated query is stored as two f16 terms (q = q_hi + q_lo, term s
+// at Qs + s * q_stride): the MFMA partner of the f16 copy of K that k_prep_kv makes.
 // ------------------------------------------------------------------------------------------------
-template <int KDT> struct SplitN { static constexpr int NS = (KDT == DT_BF16) ? 3 : 2; };
-
-template <int KDT, int NS>
-__device__ __forceinline__ void split_terms(float v, uint16_t (&t)[NS]) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        t[s] = down1<KDT>(v);
-        v -= up1<KDT>(t[s]);
-    }
-}
-
 template <int KDT>
 __global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const float *__restrict__ rope_cos,
                           const float *__restrict__ rope_sin, uint16_t *__restrict__ Qs, size_t q_stride,
                           uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, int nq, int nkv, int d, int max_seq) {
-    constexpr int NS = SplitN<KDT>::NS;
     const int half = d >> 1, per_t = (nq + 2 * nkv) * half;
     const size_t total = (size_t)T * per_t;
     const int R = (nq + 2 * nkv) * d;
@@ -632,15 +620,14 @@ __global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const fl
             v1 = y1;
         }
         if (hh < nq) {
-            uint16_t a[NS], b[NS];
-            split_terms<KDT, NS>(v0, a);
-            split_terms<KDT, NS>(v1, b);
+            uint16_t h0, l0, h1, l1;
+            split_f16(v0, h0, l0);
+            split_f16(v1, h1, l1);
             uint16_t *dst = Qs + (size_t)t * nq * d + hh * d;
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                dst[s * q_stride + i] = a[s];
-                dst[s * q_stride + i + half] = b[s];
-            }
+            dst[i] = h0;
+            dst[i + half] = h1;
+            dst[q_stride + i] = l0;
+            dst[q_stride + i + half] = l1;
         } else {
             uint16_t *dst = hh < nq + nkv ? kc + ((size_t)(hh - nq) * max_seq + pos) * d
                                           : vc + ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
@@ -650,61 +637,129 @@ __global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const fl
     }
 }
 
-// Vt[kvh][i][j] = V[kvh][j][i] for j < ctx, zero for ctx <= j < ctx_pad.  64 x 64 tiles through LDS.
+// Cache value -> f16 bits.  Every bf16 value of magnitude 2^-14 .. 65504 is an f16 value; smaller ones round
+// with an absolute error below 3e-8 and larger ones (never seen in a K or V row) saturate.
+template <int KDT> __device__ __forceinline__ uint16_t cache_to_f16(uint16_t b) {
+    if constexpr (KDT == DT_F16) return b;
+    const float v = fminf(fmaxf(up1<DT_BF16>(b), -65504.f), 65504.f);
+    return down1<DT_F16>(v);
+}
+
+// Position of key j (0..63 within a tile) in a V^T row.  k_flash_attn feeds P^T to the matrix cores straight
+// from its score accumulators, where lane half hf holds keys {4hf..4hf+3, 8+4hf..8+4hf+3} of each group of
+// 16; storing the group in that order lets the lane read its eight V values with one 128-bit load.
+__device__ __forceinline__ int vt_slot(int j) {
+    const int o = j & 15, a = o >> 3, hf = (o >> 2) & 1, e = o & 3;
+    return (j & ~15) | (8 * hf + 4 * a + e);
+}
+
+// The f16 operands of k_flash_attn for context rows 0..ctx-1 of one layer, padded with zeros to ctx_pad:
+//   Kf[kvh][j][i] = f16(K[kvh][j][i])            Vt[kvh][i][vt_slot(j)] = f16(V[kvh][j][i])
+// 64 x 64 tiles through LDS; grid (ctx_pad / 64, d / 64, n_kv).
+template <int KDT>
 __global__ void __launch_bounds__(256)
-k_transpose_v(const uint16_t *__restrict__ vc, int ctx, int ctx_pad, uint16_t *__restrict__ Vt, int d, int max_seq) {
+k_prep_kv(const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc, int ctx, int ctx_pad,
+          uint16_t *__restrict__ Kf, uint16_t *__restrict__ Vt, int d, int max_seq) {
     __shared__ uint16_t tile[64][66];
     const int kvh = blockIdx.z, j0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
-    const uint16_t *src = vc + (size_t)kvh * max_seq * d;
-    uint16_t *dst = Vt + (size_t)kvh * d * ctx_pad;
+    const uint16_t *ksrc = kc + (size_t)kvh * max_seq * d, *vsrc = vc + (size_t)kvh * max_seq * d;
+    uint16_t *kdst = Kf + (size_t)kvh * ctx_pad * d, *vdst = Vt + (size_t)kvh * d * ctx_pad;
     for (int e = threadIdx.x; e < 64 * 64; e += 256) {
         const int j = e >> 6, i = e & 63;
-        tile[j][i] = (j0 + j < ctx) ? src[(size_t)(j0 + j) * d + i0 + i] : (uint16_t)0;
+        const bool in = j0 + j < ctx;
+        kdst[(size_t)(j0 + j) * d + i0 + i] = in ? cache_to_f16<KDT>(ksrc[(size_t)(j0 + j) * d + i0 + i]) : (uint16_t)0;
+        tile[j][i] = in ? cache_to_f16<KDT>(vsrc[(size_t)(j0 + j) * d + i0 + i]) : (uint16_t)0;
     }
     __syncthreads();
     for (int e = threadIdx.x; e < 64 * 64; e += 256) {
         const int i = e >> 6, j = e & 63;
-        dst[(size_t)(i0 + i) * ctx_pad + j0 + j] = tile[j][i];
+        vdst[(size_t)(i0 + i) * ctx_pad + j0 + vt_slot(j)] = tile[j][i];
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Causal GQA flash attention.  Workgroup = one query head x 128 queries; wave = 32 queries.
+// Causal GQA flash attention in f16 operands.  Workgroup = one query head x 128 queries; wave = 32 queries.
 // Per 64-key tile:  S^T = K Q^T  (keys x queries, so a lane owns one query column and the softmax row
-// statistics need a single exchange with lane^32), online softmax in fp32, then  O^T += V^T P^T  where
-// the P^T operand is taken straight from the S^T accumulator registers: lane half h holds keys
-// {4h..4h+3, 8+4h..8+4h+3} of each 16-key group, and the V^T operand is read from LDS in that same key
-// order.  q and p enter the matrix cores as NS 16-bit terms each; K and V^T as stored.  Masked scores
-// are replaced by a finite sentinel (Appendix B.3 item 3); their probability is set to exactly zero.
+// statistics need a single exchange with lane^32), online softmax in fp32 (base 2), then  O^T += V^T P^T
+// where the P^T operand is taken straight from the S^T accumulator registers and the V^T operand is read
+// in the matching key order (vt_slot).  q and p enter the matrix cores as two f16 terms each; K and V^T are
+// exact f16 copies of the cache rows.  p carries a factor 2^8 (so that small probabilities stay f16
+// normals); it cancels in the final division.  Masked scores never reach exp: their probability is set
+// to exactly zero (Appendix B.3 item 3).
+// K and V^T tiles go from global memory straight into LDS (LDS-DMA) through two stages, one tile ahead of
+// the MFMAs, with one barrier per tile; 16-byte chunk c of row r sits in slot c ^ (r & 7) of its row, which
+// keeps the 128-bit fragment reads conflict-free.  The heaviest query blocks are scheduled first.
 // The output is written as an f16 pair (hi, lo): the A operand of the O projection.
 // ------------------------------------------------------------------------------------------------
-template <int KDT, int D>
-__global__ void __launch_bounds__(256)
-k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *__restrict__ kc,
-             const uint16_t *__restrict__ Vt, int ctx_pad, int T, int p0, uint16_t *__restrict__ Ohi,
-             uint16_t *__restrict__ Olo, int nq, int g, int max_seq, float scale) {
-    constexpr int NS = SplitN<KDT>::NS;
-    constexpr int LK = D + 8;    // K tile row stride (elements)
-    constexpr int LV = 64 + 4;   // V^T tile row stride (elements)
-    constexpr int NKS = D / 16;  // MFMA k-steps over the head dimension
-    constexpr int NDB = D / 32;  // 32-row blocks of O^T
-    __shared__ __attribute__((aligned(16))) uint16_t sK[64 * LK];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[D * LV];
+typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_rtz(float a, float b) {
+    const fp16x2 h = __builtin_amdgcn_cvt_pkrtz(a, b);
+    uint32_t u;
+    __builtin_memcpy(&u, &h, 4);
+    return u;
+}
+// (a, b) -> packed f16 head terms (round toward zero) and packed f16 terms of what they leave out
+__device__ __forceinline__ HiLo split_pack(float a, float b) {
+    const fp16x2 h = __builtin_amdgcn_cvt_pkrtz(a, b);
+    HiLo r;
+    __builtin_memcpy(&r.hi, &h, 4);
+    r.lo = pack_rtz(a - (float)h.x, b - (float)h.y);
+    return r;
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int fr = lane & 31, hf = lane >> 5;
-    const int h = blockIdx.y, kvh = h / g;
-    const int qb0 = blockIdx.x * 128;
+template <int D>
+__global__ void __launch_bounds__(256, 2)
+k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *__restrict__ Kf,
+             const uint16_t *__restrict__ Vt, int ctx_pad, int T, int p0, uint16_t *__restrict__ Ohi,
+             uint16_t *__restrict__ Olo, int nq, int g, float scale_log2e) {
+    constexpr int NKS = D / 16;        // MFMA k-steps over the head dimension
+    constexpr int NDB = D / 32;        // 32-row blocks of O^T
+    constexpr int KROW = D * 2;        // bytes of a K tile row
+    constexpr int TILE_K = 64 * KROW;  // bytes of a K tile (64 keys)
+    constexpr int TILE_V = D * 128;    // bytes of a V^T tile (D rows x 64 keys)
+    constexpr int STAGE = TILE_K + TILE_V;
+    constexpr int NI = D / 32;         // LDS-DMA instructions (1 KB each) per wave, per tile and operand
+    __shared__ __attribute__((aligned(1024))) uint8_t stages[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fr = lane & 31, hf = lane >> 5, sw = fr & 7;
+    const int nqb = (T + 127) / 128;
+    const int qb = nqb - 1 - (int)blockIdx.x / nq, h = (int)blockIdx.x % nq, kvh = h / g;
+    const int qb0 = qb * 128;
     const int tq = qb0 + wave * 32 + fr;  // this lane's query (index into the new block)
     const int qd = nq * D;
     const u32x4 zero = {0u, 0u, 0u, 0u};
 
-    u32x4 qf[NS][NKS];
+    u32x4 qf[2][NKS];
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
+    for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
             qf[s][ks] = tq < T ? ld16(Qs + s * q_stride + (size_t)tq * qd + h * D + ks * 16 + hf * 8) : zero;
+
+    const uint16_t *kbase = Kf + (size_t)kvh * ctx_pad * D;
+    const uint16_t *vbase = Vt + (size_t)kvh * D * ctx_pad;
+    // DMA plan: instruction q of a tile fills LDS bytes [1024 q, 1024 q + 1024); wave w issues q = w NI .. w NI + NI - 1
+    // of both operands.  The lane's 16 bytes are slot (byte offset % row bytes) / 16 of their row.
+    uint32_t koff[NI], voff[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int at = (wave * NI + i) * 1024 + lane * 16;
+        const int kr = at / KROW, kslot = (at % KROW) / 16;
+        koff[i] = (uint32_t)(kr * D + ((kslot ^ (kr & 7)) << 3)) * 2u;
+        const int vr = at / 128, vslot = (at % 128) / 16;
+        voff[i] = ((uint32_t)vr * (uint32_t)ctx_pad + ((vslot ^ (vr & 7)) << 3)) * 2u;
+    }
+    const uint32_t lds0 = lds_addr(stages);
+    auto issue = [&](int kt) {
+        const uint32_t st = lds0 + (kt & 1) * STAGE + wave * NI * 1024;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            lds_dma16(kbase + (size_t)kt * 64 * D, koff[i], st + i * 1024);
+            lds_dma16(vbase + (size_t)kt * 64, voff[i], st + TILE_K + i * 1024);
+        }
+    };
 
     f32x16 oacc[NDB];
 #pragma unroll
@@ -715,31 +770,20 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
 
     const int last_q = min(T, qb0 + 128) - 1;    // last query of the workgroup
     const int n_tiles = (p0 + last_q) / 64 + 1;  // key tiles 0 .. n_tiles-1 hold keys <= p0 + last_q
+    const int wave_first_pos = p0 + qb0 + wave * 32;
     const int wave_last_key = p0 + min(T - 1, qb0 + wave * 32 + 31);
-    const uint16_t *kbase = kc + (size_t)kvh * max_seq * D;
-    const uint16_t *vbase = Vt + (size_t)kvh * D * ctx_pad;
-    const int ctx = p0 + T;
+    const int qpos = p0 + tq;
 
+    issue(0);
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int key0 = kt * 64;
-        __syncthreads();  // previous tile fully consumed
-        // K tile: 64 keys x D -> 64 * D/8 vectors
-        for (int vid = tid; vid < 64 * (D / 8); vid += 256) {
-            const int r = vid / (D / 8), c = vid % (D / 8);
-            const int key = key0 + r;
-            const u32x4 v = key < ctx ? ld16(kbase + (size_t)key * D + c * 8) : zero;
-            *reinterpret_cast<u32x4 *>(sK + r * LK + c * 8) = v;
-        }
-        // V^T tile: D rows x 64 keys -> D * 8 vectors (padding columns of Vt are zero)
-        for (int vid = tid; vid < D * 8; vid += 256) {
-            const int r = vid >> 3, c = vid & 7;
-            const u32x4 v = ld16(vbase + (size_t)r * ctx_pad + key0 + c * 8);
-            u32x2 *dst = reinterpret_cast<u32x2 *>(sV + r * LV + c * 8);
-            dst[0] = u32x2{v.x, v.y};
-            dst[1] = u32x2{v.z, v.w};
-        }
+        // this wave's part of tile kt has landed; after the barrier every part has, and every wave is done with
+        // the other stage (tile kt-1), which then receives tile kt+1
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        if (kt + 1 < n_tiles) issue(kt + 1);
         if (key0 > wave_last_key) continue;  // tile entirely above this wave's diagonal (wave-uniform)
+        const uint8_t *sK = stages + (kt & 1) * STAGE, *sV = sK + TILE_K;
 
         // S^T = K Q^T : two 32-key blocks
         f32x16 sacc[2];
@@ -749,34 +793,38 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
             for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const u32x4 kf = *reinterpret_cast<const u32x4 *>(sK + (kb * 32 + fr) * LK + ks * 16 + hf * 8);
-#pragma unroll
-                for (int s = NS - 1; s >= 0; --s) sacc[kb] = mfma32<KDT>(kf, qf[s][ks], sacc[kb]);
+                const u32x4 kf = *reinterpret_cast<const u32x4 *>(sK + (kb * 32 + fr) * KROW + (((ks * 2 + hf) ^ sw) << 4));
+                sacc[kb] = mfma32<DT_F16>(kf, qf[1][ks], sacc[kb]);
+                sacc[kb] = mfma32<DT_F16>(kf, qf[0][ks], sacc[kb]);
             }
         }
-        // online softmax for this lane's query
-        const int qpos = p0 + tq;
+        // online softmax (base 2) for this lane's query
+        const bool diagonal = key0 + 63 > wave_first_pos;  // some key of the tile is masked for some query of the wave
         float mx = -1.0e30f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
-                const float sv = key <= qpos ? sacc[kb][i] * scale : -1.0e30f;
+                float sv = sacc[kb][i] * scale_log2e;
+                if (diagonal) {
+                    const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+                    sv = key <= qpos ? sv : -1.0e30f;
+                }
                 sacc[kb][i] = sv;
                 mx = fmaxf(mx, sv);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
         const float mnew = fmaxf(mrow, mx);
-        const float corr = expf(mrow - mnew);
+        const float corr = __builtin_amdgcn_exp2f(mrow - mnew);
         mrow = mnew;
+        const float shift = 8.0f - mnew;
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const float sv = sacc[kb][i];
-                const float pv = sv > -0.5e30f ? expf(sv - mnew) : 0.f;
+                const float pv = sv > -0.5e30f ? __builtin_amdgcn_exp2f(sv + shift) : 0.f;
                 sacc[kb][i] = pv;
                 psum += pv;
             }
@@ -785,29 +833,18 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int i = 0; i < 16; ++i) oacc[db][i] *= corr;
-        // O^T += V^T P^T, 16 keys per MFMA, NS terms of p
+        // O^T += V^T P^T, 16 keys per MFMA, two terms of p
 #pragma unroll
         for (int ks2 = 0; ks2 < 4; ++ks2) {
             const int kb = ks2 >> 1, ib = (ks2 & 1) * 8;
-            uint16_t pt[8][NS];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) split_terms<KDT, NS>(sacc[kb][ib + j], pt[j]);
-            u32x4 pf[NS];
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                pf[s].x = (uint32_t)pt[0][s] | ((uint32_t)pt[1][s] << 16);
-                pf[s].y = (uint32_t)pt[2][s] | ((uint32_t)pt[3][s] << 16);
-                pf[s].z = (uint32_t)pt[4][s] | ((uint32_t)pt[5][s] << 16);
-                pf[s].w = (uint32_t)pt[6][s] | ((uint32_t)pt[7][s] << 16);
-            }
+            const HiLo t0 = split_pack(sacc[kb][ib + 0], sacc[kb][ib + 1]), t1 = split_pack(sacc[kb][ib + 2], sacc[kb][ib + 3]);
+            const HiLo t2 = split_pack(sacc[kb][ib + 4], sacc[kb][ib + 5]), t3 = split_pack(sacc[kb][ib + 6], sacc[kb][ib + 7]);
+            const u32x4 ph = {t0.hi, t1.hi, t2.hi, t3.hi}, pl = {t0.lo, t1.lo, t2.lo, t3.lo};
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-                const uint16_t *vr = sV + (db * 32 + fr) * LV + ks2 * 16 + hf * 4;
-                const u32x2 v0 = *reinterpret_cast<const u32x2 *>(vr);
-                const u32x2 v1 = *reinterpret_cast<const u32x2 *>(vr + 8);
-                const u32x4 vf = {v0.x, v0.y, v1.x, v1.y};
-#pragma unroll
-                for (int s = NS - 1; s >= 0; --s) oacc[db] = mfma32<KDT>(vf, pf[s], oacc[db]);
+                const u32x4 vf = *reinterpret_cast<const u32x4 *>(sV + (db * 32 + fr) * 128 + (((ks2 * 2 + hf) ^ sw) << 4));
+                oacc[db] = mfma32<DT_F16>(vf, pl, oacc[db]);
+                oacc[db] = mfma32<DT_F16>(vf, ph, oacc[db]);
             }
         }
     }
@@ -984,28 +1021,25 @@ void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float 
                            Qs, q_stride, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
 }
 
-void launch_transpose_v(const Dims &D, const uint16_t *vc, int ctx, int ctx_pad, uint16_t *Vt, hipStream_t st) {
+void launch_prep_kv(const Dims &D, const uint16_t *kc, const uint16_t *vc, int ctx, int ctx_pad, uint16_t *Kf,
+                    uint16_t *Vt, hipStream_t st) {
     const dim3 grid(ctx_pad / 64, D.d / 64, D.nkv);
-    hipLaunchKernelGGL(k_transpose_v, grid, dim3(256), 0, st, vc, ctx, ctx_pad, Vt, D.d, D.max_seq);
-}
-
-template <int KDT>
-static void fa_d(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *kc, const uint16_t *Vt,
-                 int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st) {
-    const dim3 grid((T + 127) / 128, D.nq), block(256);
-    const float scale = 1.0f / sqrtf((float)D.d);
-    if (D.d == 128)
-        hipLaunchKernelGGL((k_flash_attn<KDT, 128>), grid, block, 0, st, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo,
-                           D.nq, D.g(), D.max_seq, scale);
+    if (D.kvdt == DT_BF16)
+        hipLaunchKernelGGL(k_prep_kv<DT_BF16>, grid, dim3(256), 0, st, kc, vc, ctx, ctx_pad, Kf, Vt, D.d, D.max_seq);
     else
-        hipLaunchKernelGGL((k_flash_attn<KDT, 64>), grid, block, 0, st, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo,
-                           D.nq, D.g(), D.max_seq, scale);
+        hipLaunchKernelGGL(k_prep_kv<DT_F16>, grid, dim3(256), 0, st, kc, vc, ctx, ctx_pad, Kf, Vt, D.d, D.max_seq);
 }
 
-void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *kc, const uint16_t *Vt,
+void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *Kf, const uint16_t *Vt,
                        int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st) {
-    if (D.kvdt == DT_BF16) fa_d<DT_BF16>(D, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo, st);
-    else fa_d<DT_F16>(D, Qs, q_stride, kc, Vt, ctx_pad, T, p0, Ohi, Olo, st);
+    const dim3 grid(((T + 127) / 128) * D.nq), block(256);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)D.d);
+    if (D.d == 128)
+        hipLaunchKernelGGL((k_flash_attn<128>), grid, block, 0, st, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, D.nq,
+                           D.g(), scale_log2e);
+    else
+        hipLaunchKernelGGL((k_flash_attn<64>), grid, block, 0, st, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, D.nq,
+                           D.g(), scale_log2e);
 }
 
 }  // namespace efm
