@@ -285,7 +285,7 @@ __global__ void k_fill_u16(uint16_t *p, size_t n, uint16_t v) {
 // Scores use a finite sentinel instead of -inf (Appendix B.3, item 3).
 // ------------------------------------------------------------------------------------------------
 constexpr float NEG_BIG = -1.0e30f;
-constexpr int ATTN_CHUNK_MIN = 128;
+constexpr int ATTN_CHUNK_MIN = 64;
 
 template <int KDT, int D, int GQ>
 __global__ void __launch_bounds__(256)
@@ -296,7 +296,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
     constexpr int RW = WAVE / LPR;   // rows per wave per load
     constexpr int UR = 4;            // loads in flight per lane (K and V each)
     constexpr int NW = 4;
-    constexpr int PS = D + 2;        // partial record: m, l, acc[D]
+    constexpr int PS = D + 4;        // partial record: m, l, two unused words, acc[D] (16-byte aligned)
     constexpr int MAX_S = 64;        // launchers never use more context slices
     __shared__ float wstate[NW][GQ][PS];
     __shared__ float sm[GQ][MAX_S], sl[GQ][MAX_S];
@@ -434,7 +434,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
             __hip_atomic_store(rec + 0, mt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(rec + 1, lt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __hip_atomic_store(rec + 2 + i, at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(rec + 4 + i, at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // every thread waits for its own stores, then one thread takes an arrival ticket
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -454,19 +454,24 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         sl[h][t] = rec[1];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < GQ * D; idx += blockDim.x) {
-        const int h = idx / D, i = idx - h * D;
-        const float *rec = part + ((size_t)(kvh * GQ + h) * S) * PS + 2 + i;
+    // four adjacent output elements per thread: one pass over the heads, 16-byte loads of the records
+    for (int idx = threadIdx.x; idx < GQ * (D / 4); idx += blockDim.x) {
+        const int h = idx / (D / 4), i = (idx - h * (D / 4)) * 4;
+        const float *rec = part + ((size_t)(kvh * GQ + h) * S) * PS + 4 + i;
         float mt = NEG_BIG;
         for (int t = 0; t < n_active; ++t) mt = fmaxf(mt, sm[h][t]);
-        float lt = 0.f, at = 0.f;
-#pragma unroll 8
+        float lt = 0.f;
+        float4 at = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 16
         for (int t = 0; t < n_active; ++t) {
             const float c = __expf(sm[h][t] - mt);
+            const float4 r = *reinterpret_cast<const float4 *>(rec + (size_t)t * PS);
             lt += sl[h][t] * c;
-            at += rec[(size_t)t * PS] * c;
+            at.x += r.x * c; at.y += r.y * c; at.z += r.z * c; at.w += r.w * c;
         }
-        o[(size_t)(kvh * GQ + h) * D + i] = at / lt;
+        const float inv = 1.0f / lt;
+        float4 *dst = reinterpret_cast<float4 *>(o + (size_t)(kvh * GQ + h) * D + i);
+        *dst = float4{at.x * inv, at.y * inv, at.z * inv, at.w * inv};
     }
     if (threadIdx.x == 0) __hip_atomic_store(&counters[kvh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -99,7 +99,7 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.q = take(qd * 4);
     L.o = take(qd * 4);
     L.h = take(I * 4);
-    L.part = take((size_t)c->n_q_heads * ATTN_SPLITS * (d + 2) * 4);
+    L.part = take((size_t)c->n_q_heads * ATTN_SPLITS * (d + 4) * 4);
     L.counters = take(c->n_kv_heads * 4);
     L.logits = take(V * 4);
     L.hidden = take(H * 4);
