@@ -40,6 +40,71 @@ def prefill_flops(shape, T):
     return 2 * T * per_tok + attn + 2 * shape.vocab * H
 
 
+def sweep(args) -> int:
+    """Secondary measurement points: every shape of the workload table, TTFT against prompt length and decode
+    latency against context length (context established by a prefill of random tokens)."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2604_27476_amd import binding
+
+    def timed_request(gm, prompt, n_decode, embeds=None):
+        stream = gm.stream
+        gm.kv_reset(0)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e2 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        gm.prefill(prompt, embeds=embeds, want_logits=False)
+        e1.record(stream)
+        for _ in range(n_decode - 1):
+            gm.decode_step(-1, sync=False)
+        gm.decode_step(-1)
+        e2.record(stream)
+        stream.synchronize()
+        return e0.elapsed_time(e1), e1.elapsed_time(e2) / n_decode
+
+    plan = [  # (shape, prompt lengths for TTFT, (context, decode steps) pairs)
+        ("qwen2.5-0.5b-shaped", [128], [(128, 256)]),
+        ("qwen2.5-1.5b-shaped", [512], [(512, 128)]),
+        ("qwen2.5-7b-shaped", [128, 512, 1024, 2048, 4096], [(256, 64), (1024, 64), (4096, 64), (8192, 64)]),
+    ]
+    for name, prompts, decodes in plan:
+        shape0 = synth.SHAPES[name]
+        need = max(prompts + [c + n for c, n in decodes]) + 8
+        shape = shape0.with_(max_seq_len=need)
+        w = synth.make_weights(shape)
+        gm = binding.Model(binding.make_config(shape), w)
+        log(f"[sweep] {name} loaded, arena {gm.arena_bytes / 1e9:.1f} GB")
+        for T in prompts:
+            prompt = synth.make_prompt(shape, T)
+            ts = [timed_request(gm, prompt, 1)[0] for _ in range(2 + args.steps)][2:]
+            tf = prefill_flops(shape, T) / (np.mean(ts) * 1e-3) / 1e12
+            print(json.dumps({"shape": name, "kind": "prefill", "prompt_tokens": T, "ttft_ms": round(float(np.mean(ts)), 3),
+                              "useful_TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_PEAK_TFLOPS, 4),
+                              "weight_stream_GBps": round(shape.weight_bytes_per_token() / (np.mean(ts) * 1e-3) / 1e9, 1)}), flush=True)
+        for C, N in decodes:
+            prompt = synth.make_prompt(shape, C)
+            ds = [timed_request(gm, prompt, N)[1] for _ in range(1 + max(2, args.steps // 2))][1:]
+            ms = float(np.mean(ds))
+            byts = shape.weight_bytes_per_token() + shape.kv_bytes_per_context_token() * (C + (N - 1) / 2.0)
+            print(json.dumps({"shape": name, "kind": "decode", "context": C, "decode_steps": N, "ms_per_token": round(ms, 4),
+                              "hbm_GBps": round(byts / (ms * 1e-3) / 1e9, 1),
+                              "frac_of_hbm_peak": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}), flush=True)
+        if name == "qwen2.5-7b-shaped":  # image rows + text ids as one prefill, short generation, latency percentiles
+            emb = torch.from_numpy(np.ascontiguousarray(synth.make_visual_embeds(shape, 1024)).view(np.int16)).to(gm.device)
+            torch.cuda.synchronize()  # the rows are resident before any timed request
+            ids = synth.make_prompt(shape, 64)
+            reps = [timed_request(gm, ids, 8, embeds=emb) for _ in range(3 + 100)][3:]
+            tt = np.array([r[0] for r in reps]); dd = np.array([r[1] for r in reps])
+            print(json.dumps({"shape": name, "kind": "vlm", "embed_rows": 1024, "text_tokens": 64, "decode_steps": 8,
+                              "ttft_ms_p50": round(float(np.percentile(tt, 50)), 3), "ttft_ms_p99": round(float(np.percentile(tt, 99)), 3),
+                              "decode_ms_per_token_p50": round(float(np.percentile(dd, 50)), 4),
+                              "decode_ms_per_token_p99": round(float(np.percentile(dd, 99)), 4), "repetitions": 100}), flush=True)
+        gm.close()
+        del gm, w
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,6 +114,9 @@ def main() -> int:
     ap.add_argument("--decode", type=int, default=64)
     ap.add_argument("--shape", default="qwen2.5-7b-shaped")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline line: TTFT over prompt lengths and decode latency over context "
+                         "lengths for every configured shape, one JSON object per line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the single-GPU hot path of a single-request system; "
@@ -64,6 +132,8 @@ def main() -> int:
         log("bench.py: no GPU visible")
         return 2
     binding.load_library()  # fails loudly if libedgefm.so is missing
+    if args.sweep:
+        return sweep(args)
 
     shape0 = synth.SHAPES[args.shape]
     T, N = args.prompt, args.decode

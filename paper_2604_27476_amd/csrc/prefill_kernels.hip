@@ -293,7 +293,9 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 
 // ------------------------------------------------------------------------------------------------
 // Pipelined GEMM (same contract as k_gemm; K must be a multiple of 32): 256 x 256 x 32 workgroup tile,
-// eight waves in 4 x 2, each wave 64 x 128 (TM = 2, TN = 4: 0.5 LDS fragment reads per MFMA).  The three
+// eight waves in 4 x 2, each wave 64 x 128 (WM = 4: TM = 2, TN = 4, 0.5 LDS fragment reads per MFMA); or, for
+// prompts that would leave most of a 256-row tile empty, 128 x 256 x 32 with the waves in 2 x 4, each 64 x 64
+// (WM = 2).  The three
 // operand tiles go from global memory straight into LDS (global_load_lds, no staging registers, no
 // ds_write) through a ring of three stages, two to three k-tiles ahead of the MFMAs, with one barrier per
 // k-tile.  LDS rows are 64 bytes (4 chunks of 16 B); chunk c of row r sits in slot c ^ ((r >> 1) & 3),
@@ -302,17 +304,17 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 // ------------------------------------------------------------------------------------------------
 constexpr int PK = 32;                     // k-tile depth
 constexpr int P_STAGES = 3;
-constexpr int P_BM = 256, P_BN = 256;
-constexpr int P_STAGE_ELEMS = (2 * P_BM + P_BN) * PK;  // A_hi | A_lo | B, f16 elements per stage (48 KB)
+constexpr int P_BN = 256;                  // tile columns; tile rows are 64 WM
+constexpr int pipe_stage_elems(int wm) { return (2 * 64 * wm + P_BN) * PK; }  // A_hi | A_lo | B, f16 elements per stage
 constexpr int PIPE_MAX_SPLITS = 8;          // k-slices per tile at most
 constexpr int PIPE_MIN_SLICE_TILES = 16;    // k-tiles per slice at least (keeps the tile prologue and epilogue small)
-static_assert((size_t)P_BM * P_BN * 4 * 256 <= GEMM_WS_BYTES, "a split round (slices x tiles <= CUs) has to fit the workspace");
+static_assert((size_t)256 * P_BN * 4 * 256 <= GEMM_WS_BYTES, "a split round (slices x tiles <= CUs) has to fit the workspace");
 
 // Which tiles a launch covers: tiles [tile_begin, tile_begin + n_tiles) of the n_mt x n_nt grid in grouped
 // order, each cut into k_splits slices along K.  With k_splits > 1 every slice leaves its partial tile in
-// ws[(slice * n_tiles + local tile)][256][256] and k_splitk_finish adds the slices up in a fixed order.
+// ws[(slice * n_tiles + local tile)][bm][256] and k_splitk_finish adds the slices up in a fixed order.
 struct PipeRange {
-    int n_mt, n_nt, tile_begin, n_tiles, k_splits;
+    int n_mt, n_nt, tile_begin, n_tiles, k_splits, bm;
     float *ws;
 };
 __device__ __forceinline__ void pipe_tile(const PipeRange &R, int tl, int &mt, int &nb) {
@@ -338,16 +340,18 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));
 }
 
-template <int BDT, int EPI>
+template <int BDT, int EPI, int WM>
 __global__ void __launch_bounds__(512)
 k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
             int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
             uint16_t *__restrict__ olo, PipeRange R) {
-    constexpr int TM = 2, TN = 4, WN = 32 * TN;
+    constexpr int TM = 2, TN = WM, WN = 32 * TN, WNW = 8 / WM;  // wave tile 64 x WN, waves WM x WNW
+    constexpr int BM = 64 * WM, STAGE_ELEMS = pipe_stage_elems(WM);
+    static_assert(WNW * WN == P_BN, "the waves of a row have to cover the tile columns");
     extern __shared__ __attribute__((aligned(1024))) uint16_t ring[];  // P_STAGES x (A_hi, A_lo, B)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WNW, wn = wave % WNW;
     // work unit = (k-slice, tile); consecutive units go to one XCD, slice-major, so that the workgroups
     // sharing an L2 walk the same k-range of neighbouring tiles
     const int units = R.n_tiles * R.k_splits, per_xcd = (units + N_XCD - 1) / N_XCD;
@@ -356,7 +360,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     const int split = unit / R.n_tiles, tl = unit - split * R.n_tiles;
     int mt, nb;
     pipe_tile(R, tl, mt, nb);
-    const int m0 = mt * P_BM;
+    const int m0 = mt * BM;
     int nk;  // k-tiles of this slice
     {
         const int nk_all = K / PK;
@@ -375,28 +379,36 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
             return min(nb * P_BN + r, N - 1);
         }
     };
-    // DMA plan: one instruction moves 16 rows x 64 B.  Wave w issues, per stage, instructions 2w and 2w+1 of
-    // each of the three tiles (rows 32w .. 32w+31).  Lane l of an instruction covers row R0 + l/4, slot l%4,
+    // DMA plan: one instruction moves 16 rows x 64 B.  Wave w issues, per stage, instructions A_I w .. A_I w + A_I - 1
+    // of the two A tiles and 2w, 2w + 1 of the B tile.  Lane l of an instruction covers row R0 + l/4, slot l%4,
     // i.e. logical chunk (l%4) ^ ((row >> 1) & 3).
-    uint32_t ga[2], gb[2];  // byte offsets of this lane's chunk at k0 = 0 (A_hi and A_lo share ga)
-    int lrow[2];
+    constexpr int A_I = BM / 128, B_I = P_BN / 128;
+    uint32_t ga[A_I], gb[B_I];  // byte offsets of this lane's chunk at k0 = 0 (A_hi and A_lo share ga)
+    int la[A_I], lb[B_I];       // LDS byte offset of the instruction's first row
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = 32 * wave + 16 * i + (lane >> 2);
+    for (int i = 0; i < A_I; ++i) {
+        const int r = 16 * (A_I * wave + i) + (lane >> 2);
         const int c = (lane & 3) ^ ((r >> 1) & 3);
         ga[i] = ((uint32_t)min(m0 + r, T - 1) * (uint32_t)K + c * 8) * 2u;
+        la[i] = 16 * (A_I * wave + i) * PK * 2;
+    }
+#pragma unroll
+    for (int i = 0; i < B_I; ++i) {
+        const int r = 16 * (B_I * wave + i) + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 1) & 3);
         gb[i] = ((uint32_t)brow(r) * (uint32_t)K + c * 8) * 2u;
-        lrow[i] = (32 * wave + 16 * i) * PK * 2;  // LDS byte offset of the instruction's first row
+        lb[i] = 16 * (B_I * wave + i) * PK * 2;
     }
     auto issue = [&](int kt) {
-        const uint32_t st = lds_addr(ring) + (kt % P_STAGES) * (P_STAGE_ELEMS * 2);
+        const uint32_t st = lds_addr(ring) + (kt % P_STAGES) * (STAGE_ELEMS * 2);
         const int k0 = kt * PK;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            lds_dma16(Ahi + k0, ga[i], st + lrow[i]);
-            lds_dma16(Alo + k0, ga[i], st + P_BM * PK * 2 + lrow[i]);
-            lds_dma16(W + k0, gb[i], st + 2 * P_BM * PK * 2 + lrow[i]);
+        for (int i = 0; i < A_I; ++i) {
+            lds_dma16(Ahi + k0, ga[i], st + la[i]);
+            lds_dma16(Alo + k0, ga[i], st + BM * PK * 2 + la[i]);
         }
+#pragma unroll
+        for (int i = 0; i < B_I; ++i) lds_dma16(W + k0, gb[i], st + 2 * BM * PK * 2 + lb[i]);
     };
 
     f32x16 acc[TM][TN];
@@ -413,18 +425,18 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         u32x4 ah[TM], al[TM], b[TN];
     };
     auto read_frag = [&](Frag &f, int kt, int ks) {
-        const uint16_t *st = ring + (kt % P_STAGES) * P_STAGE_ELEMS;
+        const uint16_t *st = ring + (kt % P_STAGES) * STAGE_ELEMS;
 #pragma unroll
         for (int t = 0; t < TM; ++t) {
             const int r = wm * 64 + t * 32 + fr;
             const int off = r * PK + (((ks * 2 + hf) ^ ((r >> 1) & 3)) << 3);
             f.ah[t] = *reinterpret_cast<const u32x4 *>(st + off);
-            f.al[t] = *reinterpret_cast<const u32x4 *>(st + P_BM * PK + off);
+            f.al[t] = *reinterpret_cast<const u32x4 *>(st + BM * PK + off);
         }
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             const int r = wn * WN + t * 32 + fr;
-            f.b[t] = *reinterpret_cast<const u32x4 *>(st + 2 * P_BM * PK + r * PK +
+            f.b[t] = *reinterpret_cast<const u32x4 *>(st + 2 * BM * PK + r * PK +
                                                       (((ks * 2 + hf) ^ ((r >> 1) & 3)) << 3));
         }
     };
@@ -453,7 +465,14 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     Frag f0, f1;
     issue(0);
     if (nk > 1) issue(1);
-    if (nk > 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    constexpr int NI = 2 * A_I + B_I;  // this wave's LDS-DMA instructions per k-tile
+    static_assert(NI == 6 || NI == 4, "the vmcnt immediates below are written for these two shapes");
+#define WAIT_ALL_BUT_ONE_TILE(extra)                                                   \
+    do {                                                                               \
+        if constexpr (NI == 6) asm volatile("s_waitcnt vmcnt(6)" extra ::: "memory");  \
+        else asm volatile("s_waitcnt vmcnt(4)" extra ::: "memory");                    \
+    } while (0)
+    if (nk > 1) WAIT_ALL_BUT_ONE_TILE("");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -470,7 +489,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
             mfma_frag(f1);
             __builtin_amdgcn_sched_barrier(0);
             // this wave's share of tile kt+1 has landed; only tile kt+2 may still be in flight
-            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            if (kt + 2 < nk) WAIT_ALL_BUT_ONE_TILE("");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();  // barrier 2kt+1
             asm volatile("" ::: "memory");
@@ -482,7 +501,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
             if (kt + 2 < nk) issue(kt + 2);
             read_frag(f0, kt, 0);
             read_frag(f1, kt, 1);
-            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)" ::: "memory");
+            if (kt + 2 < nk) WAIT_ALL_BUT_ONE_TILE(" lgkmcnt(0)");
             else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();  // barrier 2kt+1
@@ -497,9 +516,10 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         }
     }
 
+#undef WAIT_ALL_BUT_ONE_TILE
     constexpr float UNSCALE = 1.0f / W16_SCALE;
-    if (R.k_splits > 1) {  // partial sums of this k-slice, tile-local [256][256] fp32
-        float *wt = R.ws + (size_t)(split * R.n_tiles + tl) * (P_BM * P_BN);
+    if (R.k_splits > 1) {  // partial sums of this k-slice, tile-local [BM][256] fp32
+        float *wt = R.ws + (size_t)(split * R.n_tiles + tl) * (BM * P_BN);
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -557,21 +577,22 @@ k_splitk_finish(PipeRange R, int T, int N, const uint16_t *__restrict__ bias, fl
     const int tl = blockIdx.x;
     int mt, nb;
     pipe_tile(R, tl, mt, nb);
-    const size_t slice = (size_t)R.n_tiles * (P_BM * P_BN);
-    const float *wt = R.ws + (size_t)tl * (P_BM * P_BN);
+    const size_t slice = (size_t)R.n_tiles * (R.bm * P_BN);
+    const float *wt = R.ws + (size_t)tl * (R.bm * P_BN);
+    const int wn_out = 16 * (R.bm / 64);  // outputs per wave tile row: 32 TN / 2 with TN = bm / 64
     const int o = (threadIdx.x % TPR) * 4;
 #pragma unroll
     for (int pass = 0; pass < FIN_ROWS / RPI; ++pass) {
         const int row = blockIdx.y * FIN_ROWS + pass * RPI + threadIdx.x / TPR;
-        const int m = mt * P_BM + row;
+        const int m = mt * R.bm + row;
         if (m >= T) continue;
         if constexpr (EPI == EPI_SWIGLU) {
             const int j = nb * NOUT + o;
-            const int gc = (o >> 6) * 128 + (o & 63);  // gate column of the tile; its up column is 64 further
+            const int gc = (o / wn_out) * 2 * wn_out + o % wn_out;  // gate column of the tile; its up column is wn_out further
             f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = g;
             for (int sl = 0; sl < R.k_splits; ++sl) {
                 g += *reinterpret_cast<const f32x4 *>(wt + sl * slice + row * P_BN + gc);
-                u += *reinterpret_cast<const f32x4 *>(wt + sl * slice + row * P_BN + gc + 64);
+                u += *reinterpret_cast<const f32x4 *>(wt + sl * slice + row * P_BN + gc + wn_out);
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -913,17 +934,19 @@ static void gemm_tile(int epi, const uint16_t *Ahi, const uint16_t *Alo, const u
         hipLaunchKernelGGL((k_gemm<BDT, EPI_BIAS_F32, TM, TN>), grid, block, 0, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, mt, nt);
 }
 
-// The pipelined kernel needs 144 KB of dynamic LDS: raise the ceiling once; EDGEFM_GEMM=tile disables it.
+// The pipelined kernel needs up to 144 KB of dynamic LDS: raise the ceiling once; EDGEFM_GEMM=tile disables it.
 static bool gemm_pipe_enabled() {
     static int state = -1;
     if (state < 0) {
         const char *e = getenv("EDGEFM_GEMM");
         bool ok = !(e && e[0] == 't');
-        const int lds = P_STAGES * P_STAGE_ELEMS * 2;
-#define PIPE_ATTR(K) ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
-        PIPE_ATTR((k_gemm_pipe<DT_BF16, EPI_SWIGLU>)) PIPE_ATTR((k_gemm_pipe<DT_BF16, EPI_RESID>))
-        PIPE_ATTR((k_gemm_pipe<DT_BF16, EPI_BIAS_F32>)) PIPE_ATTR((k_gemm_pipe<DT_F16, EPI_SWIGLU>))
-        PIPE_ATTR((k_gemm_pipe<DT_F16, EPI_RESID>)) PIPE_ATTR((k_gemm_pipe<DT_F16, EPI_BIAS_F32>))
+#define PIPE_ATTR(BDT, EPI, WM)                                                                                \
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pipe<BDT, EPI, WM>),                \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,                                 \
+                                   P_STAGES * pipe_stage_elems(WM) * 2) == hipSuccess;
+#define PIPE_ATTR_EPI(BDT, WM) PIPE_ATTR(BDT, EPI_SWIGLU, WM) PIPE_ATTR(BDT, EPI_RESID, WM) PIPE_ATTR(BDT, EPI_BIAS_F32, WM)
+        PIPE_ATTR_EPI(DT_BF16, 4) PIPE_ATTR_EPI(DT_BF16, 2) PIPE_ATTR_EPI(DT_F16, 4) PIPE_ATTR_EPI(DT_F16, 2)
+#undef PIPE_ATTR_EPI
 #undef PIPE_ATTR
         state = ok ? 1 : 0;
     }
@@ -940,21 +963,21 @@ static int device_cu_count() {
     return n;
 }
 
-template <int BDT>
+template <int BDT, int WM>
 static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                         const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
                         hipStream_t st) {
     const int per_xcd = (R.n_tiles * R.k_splits + N_XCD - 1) / N_XCD;
     const dim3 grid(per_xcd * N_XCD), block(512);
-    const size_t lds = (size_t)P_STAGES * P_STAGE_ELEMS * 2;
+    const size_t lds = (size_t)P_STAGES * pipe_stage_elems(WM) * 2;
     if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU, WM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     else if (epi == EPI_RESID)
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID, WM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     else
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32, WM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     if (R.k_splits > 1) {
-        const dim3 fgrid(R.n_tiles, P_BM / FIN_ROWS);
+        const dim3 fgrid(R.n_tiles, R.bm / FIN_ROWS);
         if (epi == EPI_SWIGLU)
             hipLaunchKernelGGL((k_splitk_finish<BDT, EPI_SWIGLU>), fgrid, dim3(256), 0, st, R, T, N, bias, outf, ohi, olo);
         else if (epi == EPI_RESID)
@@ -964,32 +987,37 @@ static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const
     }
 }
 
+// Full rounds of tiles (one per CU) in one launch; the tiles of a partly filled last round are cut along K
+// instead, so that the round is short and busy on every CU, and their slices meet in the workspace.
+template <int BDT, int WM>
+static bool pipe_plan(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                      const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, hipStream_t st) {
+    constexpr int BM = 64 * WM;
+    const int n_mt = (T + BM - 1) / BM;
+    const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
+    const int n_cu = std::min(device_cu_count(), 256), tiles = n_mt * n_nt, nk = K / PK;
+    const int rem = tiles % n_cu, full = tiles - rem;
+    int splits = 1;
+    if (rem > 0 && ws) splits = std::min(std::min(n_cu / rem, PIPE_MAX_SPLITS), nk / PIPE_MIN_SLICE_TILES);
+    if (splits < 2) {
+        if (tiles * 2 < n_cu) return false;  // fewer than half of the CUs would work: leave it to the tile kernels
+        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, tiles, 1, BM, nullptr}, st);
+        return true;
+    }
+    if (full > 0)
+        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, full, 1, BM, nullptr}, st);
+    pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, full, rem, splits, BM, ws}, st);
+    return true;
+}
+
 template <int BDT>
-static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
-                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, hipStream_t st) {
-    const int pipe_mt = (T + P_BM - 1) / P_BM;
-    const int pipe_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
-    const size_t w_rows = epi == EPI_SWIGLU ? 2 * (size_t)N : (size_t)N;
-    const bool fits32 = std::max((size_t)T, w_rows) * (size_t)K * 2 < ((size_t)1 << 32);  // 32-bit byte offsets
-    // Pipelined kernel (one 256 x 256 tile per CU at a time) for prompts long enough to fill its row tiles.
-    // Tiles that would start a partly filled last round are cut along K instead, so that the round is short
-    // and busy on every CU; their slices meet in the workspace.
-    if (T >= 2 * P_BM && K % PK == 0 && fits32 && gemm_pipe_enabled()) {
-        const int n_cu = std::min(device_cu_count(), 256), tiles = pipe_mt * pipe_nt, nk = K / PK;
-        const int rem = tiles % n_cu, full = tiles - rem;
-        int splits = 1;
-        if (rem > 0 && ws) splits = std::min(std::min(n_cu / rem, PIPE_MAX_SPLITS), nk / PIPE_MIN_SLICE_TILES);
-        if (splits < 2) {
-            if (tiles * 4 >= n_cu * 3) {  // at least three quarters of the CUs busy in the (only) partial round
-                pipe_launch<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{pipe_mt, pipe_nt, 0, tiles, 1, nullptr}, st);
-                return;
-            }
-        } else {
-            if (full > 0)
-                pipe_launch<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{pipe_mt, pipe_nt, 0, full, 1, nullptr}, st);
-            pipe_launch<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{pipe_mt, pipe_nt, full, rem, splits, ws}, st);
-            return;
-        }
+static void gemm_rows(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                      const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, bool pipe_ok,
+                      bool rows128, hipStream_t st) {
+    if (pipe_ok) {
+        const bool done = rows128 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st)
+                                  : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st);
+        if (done) return;
     }
     // largest tile that still gives every one of the 256 CUs two workgroups
     auto count = [&](int tm, int tn) {
@@ -999,6 +1027,19 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
     if (count(2, 4) >= 512) gemm_tile<BDT, 2, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, st);
     else if (count(2, 2) >= 512) gemm_tile<BDT, 2, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, st);
     else gemm_tile<BDT, 1, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, st);
+}
+
+template <int BDT>
+static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, hipStream_t st) {
+    const size_t w_rows = epi == EPI_SWIGLU ? 2 * (size_t)N : (size_t)N;
+    const bool fits32 = std::max((size_t)T, w_rows) * (size_t)K * 2 < ((size_t)1 << 32);  // 32-bit byte offsets
+    const bool pipe_ok = K % PK == 0 && fits32 && gemm_pipe_enabled();
+    // 128-row tiles where 256-row tiles would be at least half empty in their last row of tiles (they cost
+    // about a tenth more per row, so long prompts stay with 256).  Mixing the two shapes in one GEMM (256-row
+    // body, 128-row tail, separate launches) measured slower: neither launch fills the machine.
+    const bool rows128 = T < 1024 && (T - 1) % 256 < 128;
+    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, rows128, st);
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,

@@ -367,4 +367,30 @@ def test_qwen_7b_config_prefill_128_decode_and_long_context():
     tok = P.decode(5, "ctx 4096 step 0")
     P.decode(tok, "ctx 4096 step 1")
     print(f"7B total {time.time() - t0:.1f}s worst {P.worst} strict {P.n_strict}/{P.n_checked}", flush=True)
+    # The benchmark's own request (prefill 1024, full depth) is beyond what the oracle finishes in minutes;
+    # what holds at any size is the cache invariant: the prefill of 1024 positions and the prefill of 1023
+    # followed by one decode step on the 1024th token are the same function (different kernels on the GPU:
+    # MFMA GEMMs + flash attention against GEMVs + split-context attention).
+    prompt = synth.make_prompt(shape, 1024)
+    g = P.gm
+    g.kv_reset(0)
+    n_full, l_full = g.prefill(prompt)
+    h_full = g.last_hidden().copy()
+    k_full = [g.kv_read(l, 1023) for l in (0, 13, 27)]
+    g.kv_reset(0)
+    g.prefill(prompt[:1023], want_logits=False)
+    n_step, l_step = g.decode_step(int(prompt[1023]), want_logits=True)
+    h_step = g.last_hidden().copy()
+    assert g.kv_len == 1024
+    eh, el = rel_l2(h_step, h_full), rel_l2(l_step, l_full)
+    print(f"7B prefill(1024) vs prefill(1023)+decode: hidden {eh:.2e} logits {el:.2e}", flush=True)
+    assert eh <= REL_TOL and el <= REL_TOL
+    top2 = np.sort(l_full)[-2:]
+    if top2[1] - top2[0] > MARGIN:
+        assert n_full == n_step
+    for (kf, vf), l in zip(k_full, (0, 13, 27)):
+        ks, vs = g.kv_read(l, 1023)
+        # layer 0 sees identical inputs on both paths; deeper rows may differ by a rounding step of the cache type
+        kd = np.abs(synth.from_bits(ks, shape.kv_dtype).astype(np.float64) - synth.from_bits(kf, shape.kv_dtype).astype(np.float64))
+        assert kd.max() <= 0.05 * max(1.0, float(np.abs(synth.from_bits(kf, shape.kv_dtype)).max())), f"layer {l}"
     P.close()
