@@ -284,6 +284,13 @@ __global__ void k_fill_u16(uint16_t *p, size_t n, uint16_t v) {
 // through LDS, the context slices by the last workgroup to arrive (fixed order: reproducible).
 // Scores use a finite sentinel instead of -inf (Appendix B.3, item 3).
 // ------------------------------------------------------------------------------------------------
+// A matrix for spare attention workgroups to pull into L2: the GEMV that follows has n_wg workgroups and its
+// workgroup b streams bytes [b bytes_per_wg, (b + 1) bytes_per_wg) of it (clipped to total).
+struct WarmJob {
+    const uint8_t *base;
+    size_t bytes_per_wg, total;
+    int n_wg;
+};
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int ATTN_CHUNK_MIN = 64;
 
@@ -291,7 +298,7 @@ template <int KDT, int D, int GQ>
 __global__ void __launch_bounds__(256)
 k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
               const int *__restrict__ d_pos, float *__restrict__ part, uint32_t *__restrict__ counters,
-              float *__restrict__ o, int max_seq, int S, float scale) {
+              float *__restrict__ o, int max_seq, int S, float scale, WarmJob warm) {
     constexpr int LPR = D / 8;       // lanes per row
     constexpr int RW = WAVE / LPR;   // rows per wave per load
     constexpr int UR = 4;            // loads in flight per lane (K and V each)
@@ -307,7 +314,29 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
     int chunk = (n_keys + S - 1) / S;
     if (chunk < ATTN_CHUNK_MIN) chunk = ATTN_CHUNK_MIN;
     const int n_active = (n_keys + chunk - 1) / chunk;
-    if (s >= n_active) return;
+    if (s >= n_active) {
+        // No slice of the context for this workgroup.  The attention is bound by latency and leaves HBM idle, so
+        // the spare workgroups pull the matrix of the next kernel (W_o) into L2 meanwhile: one word of every
+        // 128-byte line of the slices that the GEMV workgroups b = r, r + 8, ... will stream, r being this
+        // workgroup's XCD (workgroups go to the XCDs round-robin by linear index, and gridDim.x is a multiple of 8).
+        if (warm.base) {
+            const int r = s & 7;
+            const int first = n_active + ((r - n_active) & 7);  // first spare slice index on XCD r
+            if (first < S) {
+                const int per_kvh = (S - 1 - first) / 8 + 1;
+                const int idx = kvh * per_kvh + (s - first) / 8, n_spare = per_kvh * gridDim.y;
+                uint32_t sink = 0;
+                for (int b = r + 8 * idx; b < warm.n_wg; b += 8 * n_spare) {
+                    const size_t beg = (size_t)b * warm.bytes_per_wg;
+                    const size_t end = beg + warm.bytes_per_wg < warm.total ? beg + warm.bytes_per_wg : warm.total;
+                    for (size_t at = beg + (size_t)threadIdx.x * 128; at < end; at += 256 * 128)
+                        sink += *reinterpret_cast<const volatile uint32_t *>(warm.base + at);
+                }
+                asm volatile("" ::"v"(sink));
+            }
+        }
+        return;
+    }
     const int j0 = s * chunk, j1 = min(n_keys, j0 + chunk);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -597,13 +626,14 @@ void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st) {
 
 template <int KDT, int DD>
 static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
-                          const int *d_pos, float *part, uint32_t *counters, float *o, hipStream_t st) {
+                          const int *d_pos, float *part, uint32_t *counters, float *o, const WarmJob &warm,
+                          hipStream_t st) {
     const dim3 grid(G.attn_splits, D.nkv), block(256);
     const float scale = 1.0f / sqrtf((float)D.d);
 #define ATTN_CASE(GQ)                                                                                          \
     case GQ:                                                                                                   \
         hipLaunchKernelGGL((k_attn_decode<KDT, DD, GQ>), grid, block, 0, st, q, kc, vc, d_pos, part, counters, o, \
-                           D.max_seq, G.attn_splits, scale);                                                   \
+                           D.max_seq, G.attn_splits, scale, warm);                                             \
         break;
     switch (D.g()) {
         ATTN_CASE(1) ATTN_CASE(2) ATTN_CASE(3) ATTN_CASE(4) ATTN_CASE(5) ATTN_CASE(6) ATTN_CASE(7) ATTN_CASE(8)
@@ -613,13 +643,24 @@ static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uin
 }
 
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
-                        const int *d_pos, float *part, uint32_t *counters, float *o, hipStream_t st) {
+                        const int *d_pos, float *part, uint32_t *counters, float *o, const uint16_t *warm_w,
+                        hipStream_t st) {
+    WarmJob warm = {nullptr, 0, 0, 0};
+    static const bool warm_on = !(getenv("EDGEFM_WARM") && getenv("EDGEFM_WARM")[0] == '0');
+    // worthwhile only where the matrix fits the L2s (4 MB per XCD) with room to spare, and the slices map to XCDs
+    if (warm_w && warm_on && G.attn_splits % 8 == 0 && (size_t)D.H * D.qd() * 2 <= ((size_t)28 << 20)) {
+        const GemvGrid g = gemv_grid((D.H + 1) / 2, G.n_cu, (size_t)D.qd() * 4);  // the grid of launch_gemv_resid
+        warm.base = reinterpret_cast<const uint8_t *>(warm_w);
+        warm.bytes_per_wg = (size_t)(g.threads / 64) * 2 * D.qd() * 2;  // its workgroup b streams rows 2 nw b ..
+        warm.total = (size_t)D.H * D.qd() * 2;
+        warm.n_wg = g.blocks;
+    }
     if (D.kvdt == DT_BF16) {
-        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, st);
-        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, st);
+        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
+        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
     } else {
-        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, st);
-        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, st);
+        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
+        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
     }
 }
 

@@ -37,9 +37,10 @@ void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, co
                 const float *rope_sin, const int *d_pos, float *q, uint16_t *kcache_l, uint16_t *vcache_l,
                 hipStream_t st);
 // o <- softmax(q K^T / sqrt(d)) V over cache rows 0..pos, split over the context and merged
+// warm_w: W_o of this layer (workgroups without a context slice pull it into L2 for launch_gemv_resid) or null
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kcache_l,
                         const uint16_t *vcache_l, const int *d_pos, float *part, uint32_t *counters, float *o,
-                        hipStream_t st);
+                        const uint16_t *warm_w, hipStream_t st);
 // x <- x + W vec   (O projection: vec = o, K = n_q d;  down projection: vec = h, K = I)
 void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, const float *vec, float *x,
                        hipStream_t st);

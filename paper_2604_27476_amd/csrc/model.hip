@@ -186,7 +186,7 @@ void enqueue_decode(edgefm_model *m, hipStream_t st) {
         launch_qkv(D, m->G, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
                    m->vc(l), st);
         launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                           m->at<uint32_t>(m->L.counters), o, st);
+                           m->at<uint32_t>(m->L.counters), o, W.wo, st);
         launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st);
         launch_gateup(D, m->G, W, x, h, st);
         launch_gemv_resid(D, m->G, W.w_down, D.I, h, x, st);
@@ -620,7 +620,7 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) 
                 break;
             case EDGEFM_OP_ATTN:
                 launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                                   m->at<uint32_t>(m->L.counters), o, st);
+                                   m->at<uint32_t>(m->L.counters), o, W.wo, st);
                 break;
             case EDGEFM_OP_OPROJ: launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st); break;
             case EDGEFM_OP_GATEUP: launch_gateup(D, m->G, W, x, h, st); break;
