@@ -90,6 +90,18 @@ def sweep(args) -> int:
             print(json.dumps({"shape": name, "kind": "decode", "context": C, "decode_steps": N, "ms_per_token": round(ms, 4),
                               "hbm_GBps": round(byts / (ms * 1e-3) / 1e9, 1),
                               "frac_of_hbm_peak": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}), flush=True)
+        # vocabulary pruning: the same decode with 32768 candidate ids (lm_head streams only their rows)
+        C, N = decodes[min(1, len(decodes) - 1)]
+        subset = np.sort(np.random.default_rng(27480).choice(shape.vocab, size=32768, replace=False)).astype(np.int32)
+        gm.set_vocab_subset(subset)
+        prompt = synth.make_prompt(shape, C)
+        ds = [timed_request(gm, prompt, N)[1] for _ in range(3)][1:]
+        ms = float(np.mean(ds))
+        pruned = shape.weight_bytes_per_token() - (shape.vocab - 32768) * shape.hidden * 2
+        byts = pruned + shape.kv_bytes_per_context_token() * (C + (N - 1) / 2.0)
+        print(json.dumps({"shape": name, "kind": "decode_pruned_vocab", "candidates": 32768, "context": C, "decode_steps": N,
+                          "ms_per_token": round(ms, 4), "hbm_GBps": round(byts / (ms * 1e-3) / 1e9, 1)}), flush=True)
+        gm.set_vocab_subset(None)
         if name == "qwen2.5-7b-shaped":  # image rows + text ids as one prefill, short generation, latency percentiles
             emb = torch.from_numpy(np.ascontiguousarray(synth.make_visual_embeds(shape, 1024)).view(np.int16)).to(gm.device)
             torch.cuda.synchronize()  # the rows are resident before any timed request

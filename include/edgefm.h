@@ -85,7 +85,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *weights, v
  * on ties; Section 4.2 greedy setting).  A non-zero kv_len continues after a kept prefix (Eq. 5).
  *   token_ids_host : [n_tokens] int32, host (may be NULL when n_tokens == 0)
  *   embeds_dev     : [n_embeds, hidden] weight_dtype, device (may be NULL when n_embeds == 0)
- *   logits_host    : NULL or [vocab] float, host; last position's logits
+ *   logits_host    : NULL or [vocab] float, host; last position's logits ([n_ids] under edgefm_set_vocab_subset)
  *   next_token_host: NULL or one int32, host
  * Synchronises the stream before returning.  Errors leave kv_len unchanged. */
 int edgefm_prefill(edgefm_model *m, const int32_t *token_ids_host, uint32_t n_tokens, const void *embeds_dev,
@@ -95,7 +95,7 @@ int edgefm_prefill(edgefm_model *m, const int32_t *token_ids_host, uint32_t n_to
  * kv_len, and produce the next greedy token.  The step is one replay of a captured HIP graph whose
  * per-step parameters (position, current token) live in device memory (Section 3.10).
  *   token           : >= 0 explicit token id; -1 = the previous call's greedy token, taken on the device
- *   logits_host     : NULL or [vocab] float
+ *   logits_host     : NULL or [vocab] float ([n_ids] under edgefm_set_vocab_subset)
  *   next_token_host : NULL or one int32
  * If both host pointers are NULL the call only enqueues work and returns without synchronising, so
  * steps chain on the device; otherwise it synchronises the stream. */
@@ -107,6 +107,20 @@ int edgefm_kv_reset(edgefm_model *m, uint32_t keep_len);
 
 /* Number of valid context positions (host mirror of the device-side counter). */
 uint32_t edgefm_kv_len(const edgefm_model *m);
+
+/* Vocabulary pruning (named among the system-level optimisations of Section 3.2; the paper gives no
+ * definition, this one is ours): restrict the output distribution to a candidate set of token ids.
+ * From the next call on, prefill and decode stream only those rows of lm_head (its share of a decode
+ * step's bytes: 7.7 % for the 7B shape, 27.6 % for the 0.5B shape), the greedy token is the argmax over
+ * the candidates (lowest id on ties), and `logits_host` receives n_ids values, logits_host[i] belonging
+ * to token ids_host[i].  Input tokens are not restricted.
+ *   ids_host : [n_ids] int32, host, strictly ascending, each in [0, vocab); copied before returning
+ *   n_ids    : 0 (ids_host may be NULL) restores the whole vocabulary
+ * Synchronises the stream; the next decode step re-captures its graph.  A pending device-side greedy
+ * token is dropped (pass the token explicitly to the next edgefm_decode_step).
+ * Errors: INVALID_ARG (NULL, n_ids > vocab, ids not ascending), BAD_TOKEN (id out of range), STATE (the
+ * opt-in fused decode step is active); the previous setting stays in force. */
+int edgefm_set_vocab_subset(edgefm_model *m, const int32_t *ids_host, uint32_t n_ids);
 
 /* Destroy the handle (graph objects, pinned staging).  The arena is the caller's. */
 void edgefm_model_free(edgefm_model *m);

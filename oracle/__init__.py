@@ -239,3 +239,18 @@ class OracleModel:
 
     def decode_step(self, token: int, **kw):
         return self.forward(np.array([token], dtype=np.int32), None, **kw)
+
+
+def restricted_argmax(logits, subset):
+    """Greedy choice under vocabulary pruning: the candidate with the largest logit, the lowest token id on
+    ties.  `subset` holds ascending token ids.  Returns (token id, logits of the candidates in subset order).
+    The paper names vocabulary pruning (Section 3.2) without defining it; this is the definition the library
+    documents: the forward pass is unchanged and only the output distribution is restricted."""
+    logits = np.asarray(logits)
+    subset = np.asarray(subset, dtype=np.int64)
+    cand = logits[subset]
+    best = None
+    for tok, val in zip(subset.tolist(), cand.tolist()):  # plain scan: first maximum wins
+        if best is None or val > best[1]:
+            best = (tok, val)
+    return best[0], cand

@@ -26,7 +26,7 @@ EXPORTS = [
     "edgefm_query_sizes", "edgefm_model_load", "edgefm_prefill", "edgefm_decode_step", "edgefm_kv_reset",
     "edgefm_kv_len", "edgefm_model_free", "edgefm_strerror", "edgefm_last_hip_error", "edgefm_debug_kv_read",
     "edgefm_debug_kv_write", "edgefm_debug_kv_fill", "edgefm_debug_set_kv_len", "edgefm_debug_last_hidden",
-    "edgefm_debug_launch_op", "edgefm_debug_stage_trace",
+    "edgefm_debug_launch_op", "edgefm_debug_stage_trace", "edgefm_set_vocab_subset",
 ]
 
 
@@ -171,6 +171,7 @@ class Model:
         self.h = h
         del keep  # the library copied the parameters into the arena
         self._logits = np.empty(cfg.vocab, dtype=np.float32)
+        self.n_logits = int(cfg.vocab)
         self._next = np.zeros(1, dtype=np.int32)
 
     def close(self):
@@ -201,7 +202,14 @@ class Model:
                                      None if emb is None else C.c_void_p(emb.data_ptr()), n_emb,
                                      _np_ptr(self._logits) if want_logits else None, _np_ptr(self._next))
         _check(st, "edgefm_prefill")
-        return int(self._next[0]), (self._logits.copy() if want_logits else None)
+        return int(self._next[0]), (self._logits[:self.n_logits].copy() if want_logits else None)
+
+    def set_vocab_subset(self, ids=None):
+        """edgefm_set_vocab_subset: ascending candidate token ids (None or empty = whole vocabulary)."""
+        arr = np.zeros(0, np.int32) if ids is None else np.ascontiguousarray(ids, dtype=np.int32)
+        _check(self.lib.edgefm_set_vocab_subset(self.h, _np_ptr(arr) if arr.size else None, arr.size),
+               "edgefm_set_vocab_subset")
+        self.n_logits = int(arr.size) if arr.size else int(self.cfg.vocab)
 
     def decode_step(self, token: int = -1, want_logits=False, sync=True):
         """edgefm_decode_step.  sync=False enqueues only (device-chained greedy decoding)."""
@@ -211,7 +219,7 @@ class Model:
         st = self.lib.edgefm_decode_step(self.h, token, _np_ptr(self._logits) if want_logits else None,
                                          _np_ptr(self._next))
         _check(st, "edgefm_decode_step")
-        return int(self._next[0]), (self._logits.copy() if want_logits else None)
+        return int(self._next[0]), (self._logits[:self.n_logits].copy() if want_logits else None)
 
     def kv_reset(self, keep_len: int = 0):
         _check(self.lib.edgefm_kv_reset(self.h, keep_len), "edgefm_kv_reset")

@@ -179,18 +179,21 @@ template <int DT>
 __global__ void __launch_bounds__(1024)
 k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
          float *__restrict__ logits, float *__restrict__ hidden, float *__restrict__ part_val,
-         int *__restrict__ part_idx, int H, int V, float eps) {
+         int *__restrict__ part_idx, int H, int V, float eps, const int *__restrict__ subset) {
     extern __shared__ float4 smem[];
     __shared__ float red[32];
     __shared__ float bv[16];
     __shared__ int bi[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int nvec = H >> 3;
+    // V = number of candidate rows: the whole vocabulary, or the length of `subset` (ascending token ids; logits
+    // are then stored in subset order and the argmax reports token ids)
     const int n_units = (V + 1) >> 1;
     const int unit0 = blockIdx.x * nw + wave;
+    auto token_of = [&](int i) { return subset ? subset[i] : i; };
     Chunk<2, 7> pre;
     if (unit0 < n_units) {
-        const uint16_t *rows[2] = {W + (size_t)(2 * unit0) * H, W + (size_t)min(2 * unit0 + 1, V - 1) * H};
+        const uint16_t *rows[2] = {W + (size_t)token_of(2 * unit0) * H, W + (size_t)token_of(min(2 * unit0 + 1, V - 1)) * H};
         chunk_load<2, 7>(pre, rows, lane, nvec);
     }
     stage_vec<DT, true>(x, gain, H, eps, smem, red);
@@ -204,15 +207,16 @@ k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
     int best_i = 0x7fffffff;
     for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int r0 = 2 * unit, r1 = min(2 * unit + 1, V - 1);
-        const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)r1 * H};
+        const int t0 = token_of(r0), t1 = token_of(r1);
+        const uint16_t *rows[2] = {W + (size_t)t0 * H, W + (size_t)t1 * H};
         float o[2];
         wave_dots<DT, 2, 7>(rows, smem, nvec, lane, o, pre, unit == unit0);
         if (lane == 0) {
             logits[r0] = o[0];
-            if (o[0] > best) { best = o[0]; best_i = r0; }   // rows visited in increasing order per wave
+            if (o[0] > best) { best = o[0]; best_i = t0; }   // token ids visited in increasing order per wave
             if (r1 != r0) {
                 logits[r1] = o[1];
-                if (o[1] > best) { best = o[1]; best_i = r1; }
+                if (o[1] > best) { best = o[1]; best_i = t1; }
             }
         }
     }
@@ -597,12 +601,14 @@ int lmhead_blocks(const Dims &D, const Geo &G) {
 }
 
 void launch_lmhead(const Dims &D, const Geo &G, const uint16_t *lm, const uint16_t *final_norm, const float *x,
-                   float *logits, float *hidden, float *part_val, int *part_idx, int *n_part, hipStream_t st) {
+                   float *logits, float *hidden, float *part_val, int *part_idx, int *n_part, const int *subset,
+                   int n_subset, hipStream_t st) {
     const size_t lds = (size_t)D.H * 4;
-    const GemvGrid g = gemv_grid((D.V + 1) / 2, G.n_cu, lds);
+    const int n_rows = subset ? n_subset : D.V;
+    const GemvGrid g = gemv_grid((n_rows + 1) / 2, G.n_cu, lds);
     *n_part = g.blocks;
     DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_lmhead<DT>, dim3(g.blocks), dim3(g.threads), lds, st, lm, final_norm, x,
-                                        logits, hidden, part_val, part_idx, D.H, D.V, D.eps);)
+                                        logits, hidden, part_val, part_idx, D.H, n_rows, D.eps, subset);)
 }
 
 void launch_finish(const float *part_val, const int *part_idx, int n_part, int *d_next, int *d_token, int *d_pos,

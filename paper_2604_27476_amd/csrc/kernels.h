@@ -46,9 +46,11 @@ void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, co
                        hipStream_t st);
 // h <- silu(Wg RMSNorm(x)) * (Wu RMSNorm(x))
 void launch_gateup(const Dims &D, const Geo &G, const LayerW &W, const float *x, float *h, hipStream_t st);
-// logits <- Wlm RMSNorm(x) ; hidden <- RMSNorm(x) ; per-block (max, index) partials
+// logits <- Wlm RMSNorm(x) ; hidden <- RMSNorm(x) ; per-block (max, token id) partials.  With a subset (ascending
+// token ids, device memory) only those rows are streamed and logits[i] belongs to token subset[i].
 void launch_lmhead(const Dims &D, const Geo &G, const uint16_t *lm, const uint16_t *final_norm, const float *x,
-                   float *logits, float *hidden, float *part_val, int *part_idx, int *n_part, hipStream_t st);
+                   float *logits, float *hidden, float *part_val, int *part_idx, int *n_part, const int *subset,
+                   int n_subset, hipStream_t st);
 // next <- argmax (lowest index on ties); token <- next; pos <- pos + advance
 void launch_finish(const float *part_val, const int *part_idx, int n_part, int *d_next, int *d_token, int *d_pos,
                    int advance, hipStream_t st);

@@ -30,6 +30,7 @@ struct Layout {
     size_t qkv_raw, layer_table, sync, trace;  // fused decode step
     // prefill scratch
     size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Kf, Vt, tok, gemm_ws;
+    size_t subset;  // [vocab] int32: candidate token ids of a pruned vocabulary
     size_t total;
 };
 
@@ -124,6 +125,7 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.Vt = take(kvd * ctx_pad * 2);
     L.tok = take(Tm * 4);
     L.gemm_ws = take(GEMM_WS_BYTES);
+    L.subset = take(V * 4);
     L.total = off;
 }
 
@@ -150,6 +152,7 @@ struct edgefm_model {
     float *pin_logits; // [vocab]
     int32_t *pin_next; // [1]
     int n_part;        // lm_head partial count
+    uint32_t n_subset; // candidate tokens of a pruned vocabulary (0 = the whole vocabulary)
     std::vector<LayerW> LW;
     struct PrefillW { const uint16_t *wqkv, *wo, *w_gate_up, *w_down; };
     std::vector<PrefillW> PW;
@@ -192,7 +195,8 @@ void enqueue_decode(edgefm_model *m, hipStream_t st) {
         launch_gemv_resid(D, m->G, W.w_down, D.I, h, x, st);
     }
     launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), x, m->at<float>(m->L.logits),
-                  m->at<float>(m->L.hidden), m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), &m->n_part, st);
+                  m->at<float>(m->L.hidden), m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), &m->n_part,
+                  m->n_subset ? m->at<int>(m->L.subset) : nullptr, (int)m->n_subset, st);
     launch_finish(m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), m->n_part, m->d_next(), m->d_token(),
                   m->d_pos(), 1, st);
 }
@@ -210,9 +214,11 @@ int build_graph(edgefm_model *m) {
     return EDGEFM_OK;
 }
 
+size_t n_logits(const edgefm_model *m) { return m->n_subset ? m->n_subset : (size_t)m->D.V; }
+
 int fetch_outputs(edgefm_model *m, float *logits_host, int32_t *next_host) {
     if (logits_host)
-        HIPCHK(m, hipMemcpyAsync(m->pin_logits, m->at<float>(m->L.logits), (size_t)m->D.V * 4, hipMemcpyDeviceToHost,
+        HIPCHK(m, hipMemcpyAsync(m->pin_logits, m->at<float>(m->L.logits), n_logits(m) * 4, hipMemcpyDeviceToHost,
                                  m->stream));
     if (next_host) HIPCHK(m, hipMemcpyAsync(m->pin_next, m->d_next(), 4, hipMemcpyDeviceToHost, m->stream));
     if (m->use_mega)
@@ -226,7 +232,7 @@ int fetch_outputs(edgefm_model *m, float *logits_host, int32_t *next_host) {
         m->last_hip = (int)hipErrorLaunchTimeOut;
         return EDGEFM_ERR_HIP;
     }
-    if (logits_host) memcpy(logits_host, m->pin_logits, (size_t)m->D.V * 4);
+    if (logits_host) memcpy(logits_host, m->pin_logits, n_logits(m) * 4);
     if (next_host) *next_host = *m->pin_next;
     return EDGEFM_OK;
 }
@@ -274,6 +280,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     const char *ng = getenv("EDGEFM_NO_GRAPH");
     m->use_graph = !(ng && ng[0] == '1');
     m->kv_len = 0;
+    m->n_subset = 0;
     m->have_prev_token = false;
     m->last_hip = 0;
     m->pin_tok = nullptr;
@@ -472,7 +479,7 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     // only the last position needs logits: final norm + lm_head as a GEMV on that row
     launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), X + (size_t)(T - 1) * D.H,
                   m->at<float>(m->L.logits), m->at<float>(m->L.hidden), m->at<float>(m->L.part_val),
-                  m->at<int>(m->L.part_idx), &m->n_part, st);
+                  m->at<int>(m->L.part_idx), &m->n_part, m->n_subset ? m->at<int>(m->L.subset) : nullptr, (int)m->n_subset, st);
     launch_finish(m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), m->n_part, m->d_next(), m->d_token(),
                   m->d_pos(), 0, st);
     launch_set_int(m->d_pos(), ctx, st);
@@ -513,6 +520,31 @@ int edgefm_kv_reset(edgefm_model *m, uint32_t keep_len) {
     HIPCHK(m, hipGetLastError());
     m->kv_len = keep_len;
     m->have_prev_token = false;
+    return EDGEFM_OK;
+}
+
+int edgefm_set_vocab_subset(edgefm_model *m, const int32_t *ids_host, uint32_t n_ids) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    if (n_ids > 0 && !ids_host) return EDGEFM_ERR_INVALID_ARG;
+    if (n_ids > m->cfg.vocab) return EDGEFM_ERR_INVALID_ARG;
+    if (m->use_mega && n_ids > 0) return EDGEFM_ERR_STATE;  // the fused step always scores the whole vocabulary
+    for (uint32_t i = 0; i < n_ids; ++i) {
+        if (ids_host[i] < 0 || (uint32_t)ids_host[i] >= m->cfg.vocab) return EDGEFM_ERR_BAD_TOKEN;
+        if (i > 0 && ids_host[i] <= ids_host[i - 1]) return EDGEFM_ERR_INVALID_ARG;  // strictly ascending
+    }
+    // the captured step holds the lm_head grid and row count of the previous setting
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
+    if (m->graph) (void)hipGraphDestroy(m->graph);
+    m->graph_exec = nullptr;
+    m->graph = nullptr;
+    m->graph_ready = false;
+    if (n_ids > 0) {
+        HIPCHK(m, hipMemcpyAsync(m->at<int>(m->L.subset), ids_host, (size_t)n_ids * 4, hipMemcpyHostToDevice, m->stream));
+        HIPCHK(m, hipStreamSynchronize(m->stream));  // ids_host is the caller's again
+    }
+    m->n_subset = n_ids;
+    m->have_prev_token = false;  // a token chosen under the previous candidate set is not carried over
     return EDGEFM_OK;
 }
 
@@ -628,7 +660,7 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) 
             case EDGEFM_OP_LMHEAD:
                 launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), x, m->at<float>(m->L.logits),
                               m->at<float>(m->L.hidden), m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx),
-                              &m->n_part, st);
+                              &m->n_part, m->n_subset ? m->at<int>(m->L.subset) : nullptr, (int)m->n_subset, st);
                 break;
             case EDGEFM_OP_COPY: {  // layer l's gate/up weights -> its f16 prefill copy region and back is not
                                     // wanted: copy into the prefill scratch instead (same size class)

@@ -71,6 +71,12 @@ def test_null_arguments_are_errors_not_crashes(lib):
     assert not h.value
 
 
+def test_vocab_subset_rejects_null_handle(lib):
+    import ctypes as C
+    ids = (C.c_int32 * 2)(1, 2)
+    assert lib.edgefm_set_vocab_subset(None, ids, 2) == binding.EDGEFM_ERR_INVALID_ARG
+
+
 def test_strerror_covers_every_status(lib):
     seen = set()
     for code in range(0, -7, -1):

@@ -281,6 +281,85 @@ def test_error_paths_leave_state_unchanged():
     gm.close()
 
 
+def test_vocab_subset_restricts_logits_and_argmax():
+    """edgefm_set_vocab_subset: logits of the candidates (in candidate order) and the greedy token against the
+    oracle's full logits restricted to the same set; clearing the set restores the whole vocabulary."""
+    shape = TINY_BF16.with_(max_seq_len=64)
+    P = Pair(shape)
+    g, o = P.gm, P.om
+    rng = np.random.default_rng(11)
+    prompt = synth.make_prompt(shape, 20)
+    for n_ids in (1, 2, 3, 301, shape.vocab):
+        subset = np.sort(rng.choice(shape.vocab, size=n_ids, replace=False)).astype(np.int32)
+        g.set_vocab_subset(subset)
+        g.kv_reset(0); o.kv_reset(0)
+        ref = o.prefill(prompt)
+        tok_g, lg = g.prefill(prompt)
+        for step in range(4):
+            want, cand = oracle.restricted_argmax(ref["logits"], subset)
+            assert lg.shape == (n_ids,)
+            assert rel_l2(lg, cand) <= REL_TOL
+            assert tok_g in subset
+            top = np.sort(cand)[-2:]
+            if n_ids == 1 or top[1] - top[0] > MARGIN:
+                assert tok_g == want, f"n_ids {n_ids} step {step}"
+            ref = o.decode_step(want)                 # teacher-forced with the oracle's restricted choice
+            tok_g, lg = g.decode_step(want, want_logits=True)
+    # device-chained greedy under a subset equals explicit feeding
+    subset = np.sort(rng.choice(shape.vocab, size=97, replace=False)).astype(np.int32)
+    g.set_vocab_subset(subset)
+    g.kv_reset(0)
+    t, _ = g.prefill(prompt)
+    explicit = [t]
+    for _ in range(5):
+        t, _ = g.decode_step(t)
+        explicit.append(t)
+    g.kv_reset(0)
+    t, _ = g.prefill(prompt)
+    chained = [t]
+    for _ in range(5):
+        t, _ = g.decode_step(-1)
+        chained.append(t)
+    assert chained == explicit and all(x in subset for x in chained)
+    # error paths keep the previous setting; clearing restores full-vocabulary logits
+    E = binding.EdgefmError
+    for bad in ([3, 3], [5, 2], [-1, 4], [0, shape.vocab]):
+        with pytest.raises(E):
+            g.set_vocab_subset(np.array(bad, np.int32))
+    assert g.n_logits == 97
+    g.set_vocab_subset(None)
+    with pytest.raises(E) as e:
+        g.decode_step(-1)                             # the pending token was dropped with the old candidate set
+    assert e.value.status == binding.EDGEFM_ERR_STATE
+    g.kv_reset(0); o.kv_reset(0)
+    ref = o.prefill(prompt)
+    tok_g, lg = g.prefill(prompt)
+    assert lg.shape == (shape.vocab,) and rel_l2(lg, ref["logits"]) <= REL_TOL
+    P.close()
+
+
+def test_vocab_subset_at_7b_width():
+    """A 32768-candidate subset of the 152064-token vocabulary on the 7B-shaped width (two layers): the launch
+    shape the pruned lm_head has at full size."""
+    shape = synth.QWEN_7B.with_(max_seq_len=80)
+    P = Pair(shape, n_layers=2, sentinel=False)
+    rng = np.random.default_rng(12)
+    subset = np.sort(rng.choice(shape.vocab, size=32768, replace=False)).astype(np.int32)
+    P.gm.set_vocab_subset(subset)
+    prompt = synth.make_prompt(shape, 48)
+    ref = P.om.prefill(prompt)
+    tok_g, lg = P.gm.prefill(prompt)
+    for step in range(3):
+        want, cand = oracle.restricted_argmax(ref["logits"], subset)
+        assert rel_l2(lg, cand) <= REL_TOL
+        top = np.sort(cand)[-2:]
+        if top[1] - top[0] > MARGIN:
+            assert tok_g == want
+        ref = P.om.decode_step(want)
+        tok_g, lg = P.gm.decode_step(want, want_logits=True)
+    P.close()
+
+
 # --------------------------------------------------------------------------------------------------
 # decode attention over long injected contexts (split-context path at its real sizes)
 # --------------------------------------------------------------------------------------------------

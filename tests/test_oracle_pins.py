@@ -393,3 +393,24 @@ def test_fp32_build_of_same_source_is_close():
     a = oracle.OracleModel(shape, w, kind="f64").prefill(tokens, logits="all")
     b = oracle.OracleModel(shape, w, kind="f32").prefill(tokens, logits="all")
     assert rel_l2(b["hidden"], a["hidden"]) < 2e-5 and rel_l2(b["logits"], a["logits"]) < 2e-5
+
+
+def test_restricted_argmax_is_the_brute_force_choice():
+    """Vocabulary pruning as the library documents it: the argmax over the candidate ids, lowest id on ties.
+    Pinned against numpy on random logits and on planted ties."""
+    rng = np.random.default_rng(5)
+    for trial in range(50):
+        V = int(rng.integers(5, 400))
+        logits = rng.standard_normal(V).astype(np.float32)
+        n = int(rng.integers(1, V + 1))
+        subset = np.sort(rng.choice(V, size=n, replace=False))
+        if trial % 3 == 0 and n >= 2:  # plant a tie at the maximum between two candidates
+            a, b = rng.choice(n, size=2, replace=False)
+            logits[subset[a]] = logits[subset[b]] = logits.max() + 1.0
+        tok, cand = oracle.restricted_argmax(logits, subset)
+        np.testing.assert_array_equal(cand, logits[subset])
+        assert tok == int(subset[int(np.argmax(logits[subset]))])  # numpy's argmax also takes the first maximum
+        assert tok in subset and logits[tok] == logits[subset].max()
+    full = np.arange(17)
+    lg = rng.standard_normal(17)
+    assert oracle.restricted_argmax(lg, full)[0] == int(np.argmax(lg))
