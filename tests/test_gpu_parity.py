@@ -397,6 +397,15 @@ def test_long_prefill_7b_width_two_layers():
     t0 = time.time()
     P.prefill(synth.make_prompt(shape, 2048), where="T=2048")
     P.check_kv([0, 1], [0, 1, 1023, 2047])
+    # prompt lengths that take the other GEMM tile shapes: three ragged 128-row tiles (300), a ragged pair of
+    # 256-row tiles with cut last rounds (449), and an appended block on top of a kept prefix (300 + 77)
+    for T in (300, 449):
+        P.om.kv_reset(0); P.gm.kv_reset(0)
+        P.prefill(synth.make_prompt(shape, T, seed=synth.SEED_PROMPT + T), where=f"T={T}")
+        P.check_kv([0, 1], [0, T - 1])
+    P.om.kv_reset(300); P.gm.kv_reset(300)
+    P.prefill(synth.make_prompt(shape, 77, seed=5), where="T=300+77")
+    P.check_kv([1], [299, 300, 376])
     P.om.kv_reset(0); P.gm.kv_reset(0)
     P.run(synth.make_prompt(shape, 64), 8, embeds=synth.make_visual_embeds(shape, 1024))
     assert P.gm.kv_len == 1024 + 64 + 8
