@@ -102,6 +102,20 @@ def sweep(args) -> int:
         print(json.dumps({"shape": name, "kind": "decode_pruned_vocab", "candidates": 32768, "context": C, "decode_steps": N,
                           "ms_per_token": round(ms, 4), "hbm_GBps": round(byts / (ms * 1e-3) / 1e9, 1)}), flush=True)
         gm.set_vocab_subset(None)
+        # verify step of speculative decoding: m proposed tokens in one pass on top of the same context
+        gm.kv_reset(0)
+        gm.prefill(prompt, want_logits=False)
+        for mm in (2, 4, 8, 16, 32):
+            block = synth.make_prompt(shape, mm, seed=27481)
+            ts = []
+            for _ in range(6):
+                gm.kv_reset(C)
+                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(gm.stream); gm.verify_step(block); e1.record(gm.stream); gm.stream.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            print(json.dumps({"shape": name, "kind": "verify_step", "context": C, "block_tokens": mm,
+                              "ms_per_step": round(float(np.mean(ts[2:])), 4),
+                              "ms_per_token_if_all_accepted": round(float(np.mean(ts[2:])) / mm, 4)}), flush=True)
         if name == "qwen2.5-7b-shaped":  # image rows + text ids as one prefill, short generation, latency percentiles
             emb = torch.from_numpy(np.ascontiguousarray(synth.make_visual_embeds(shape, 1024)).view(np.int16)).to(gm.device)
             torch.cuda.synchronize()  # the rows are resident before any timed request

@@ -101,6 +101,20 @@ int edgefm_prefill(edgefm_model *m, const int32_t *token_ids_host, uint32_t n_to
  * steps chain on the device; otherwise it synchronises the stream. */
 int edgefm_decode_step(edgefm_model *m, int32_t token, float *logits_host, int32_t *next_token_host);
 
+/* Verification pass of speculative decoding (Section 3.11, the step that evaluates a proposed block with the
+ * base model): evaluate n_tokens given tokens at positions kv_len .. kv_len + n_tokens - 1 in one pass
+ * that streams the weights once, append their K/V, and return the base model's greedy prediction after
+ * EVERY one of them.  Equivalent to n_tokens calls of edgefm_decode_step with explicit tokens.  The
+ * caller compares next_tokens_host[i] with the proposal for position i + 1, keeps the agreeing prefix
+ * and drops the rest with edgefm_kv_reset(keep_len) ("commit": the cache advances by what was accepted).
+ *   token_ids_host   : [n_tokens] int32, host; 1 <= n_tokens <= 32
+ *   logits_host      : NULL or [n_tokens][vocab] float, host ([n_tokens][n_ids] under edgefm_set_vocab_subset)
+ *   next_tokens_host : NULL or [n_tokens] int32, host
+ * Synchronises the stream.  The last position's token is also the device-side token of a following
+ * edgefm_decode_step(-1).  Errors (INVALID_ARG, BAD_TOKEN, CONTEXT_OVERFLOW, HIP) leave kv_len unchanged. */
+int edgefm_verify_step(edgefm_model *m, const int32_t *token_ids_host, uint32_t n_tokens, float *logits_host,
+                       int32_t *next_tokens_host);
+
 /* Release or recycle the KV slot (Section 3.7; Section 3.9 fixed-prefix reuse): keep the first
  * keep_len positions, forget the rest.  keep_len == 0 is a full reset.  Constant time. */
 int edgefm_kv_reset(edgefm_model *m, uint32_t keep_len);
@@ -143,6 +157,9 @@ int edgefm_debug_kv_fill(edgefm_model *m, uint16_t pattern);
 int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n);
 /* Final-norm output ("final hidden state") of the most recent prefill / decode step: [hidden] float. */
 int edgefm_debug_last_hidden(edgefm_model *m, float *hidden_host);
+/* Final hidden state (after the final RMSNorm) of position `row` of the last edgefm_verify_step; valid until the
+ * next prefill or verify call. */
+int edgefm_debug_verify_hidden(edgefm_model *m, uint32_t row, float *hidden_host);
 
 /* Stage time stamps of the most recent fused decode step (only when the library was loaded with the
  * environment variable EDGEFM_TRACE=1 and the shape uses the fused step kernel, else EDGEFM_ERR_STATE):

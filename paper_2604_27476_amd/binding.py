@@ -26,7 +26,8 @@ EXPORTS = [
     "edgefm_query_sizes", "edgefm_model_load", "edgefm_prefill", "edgefm_decode_step", "edgefm_kv_reset",
     "edgefm_kv_len", "edgefm_model_free", "edgefm_strerror", "edgefm_last_hip_error", "edgefm_debug_kv_read",
     "edgefm_debug_kv_write", "edgefm_debug_kv_fill", "edgefm_debug_set_kv_len", "edgefm_debug_last_hidden",
-    "edgefm_debug_launch_op", "edgefm_debug_stage_trace", "edgefm_set_vocab_subset",
+    "edgefm_debug_launch_op", "edgefm_debug_stage_trace", "edgefm_set_vocab_subset", "edgefm_verify_step",
+    "edgefm_debug_verify_hidden",
 ]
 
 
@@ -203,6 +204,20 @@ class Model:
                                      _np_ptr(self._logits) if want_logits else None, _np_ptr(self._next))
         _check(st, "edgefm_prefill")
         return int(self._next[0]), (self._logits[:self.n_logits].copy() if want_logits else None)
+
+    def verify_step(self, tokens, want_logits=False):
+        """edgefm_verify_step: (next token after each given token [m], logits [m, n_logits] or None)."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        nxt = np.empty(tok.size, dtype=np.int32)
+        lg = np.empty((tok.size, self.n_logits), dtype=np.float32) if want_logits else None
+        _check(self.lib.edgefm_verify_step(self.h, _np_ptr(tok) if tok.size else None, tok.size,
+                                           _np_ptr(lg) if want_logits else None, _np_ptr(nxt)), "edgefm_verify_step")
+        return nxt, lg
+
+    def verify_hidden(self, row: int) -> np.ndarray:
+        out = np.empty(self.cfg.hidden, dtype=np.float32)
+        _check(self.lib.edgefm_debug_verify_hidden(self.h, row, _np_ptr(out)), "edgefm_debug_verify_hidden")
+        return out
 
     def set_vocab_subset(self, ids=None):
         """edgefm_set_vocab_subset: ascending candidate token ids (None or empty = whole vocabulary)."""

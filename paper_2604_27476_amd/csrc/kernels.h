@@ -124,4 +124,12 @@ void launch_prep_kv(const Dims &D, const uint16_t *kcache_l, const uint16_t *vca
 void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *Kf, const uint16_t *Vt,
                        int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st);
 
+// next_rows[t] <- argmax_i logits[t][i] over the vocabulary or the candidate ids (lowest id on ties);
+// d_next, d_token <- next_rows[T-1]
+void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, int *next_rows, int *d_next,
+                        int *d_token, hipStream_t st);
+// out[t][i] <- logits[t][subset[i]]
+void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,
+                          hipStream_t st);
+
 }  // namespace efm

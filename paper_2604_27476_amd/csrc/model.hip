@@ -31,11 +31,13 @@ struct Layout {
     // prefill scratch
     size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Kf, Vt, tok, gemm_ws;
     size_t subset;  // [vocab] int32: candidate token ids of a pruned vocabulary
+    size_t p_lm, vlogits, vgather, vnext;  // verify step: f16 copy of lm_head, [32][vocab] logits (raw, gathered), tokens
     size_t total;
 };
 
 constexpr int ATTN_SPLITS = 64;
 constexpr int MAX_PARTIALS = 4096;
+constexpr uint32_t VERIFY_MAX = 32;  // positions per verify step (sizes its logits buffers)
 
 struct Sizes {
     size_t layer_kv;  // elements of one layer of K (or V)
@@ -126,6 +128,10 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.tok = take(Tm * 4);
     L.gemm_ws = take(GEMM_WS_BYTES);
     L.subset = take(V * 4);
+    L.p_lm = take(V * H * 2);
+    L.vlogits = take((size_t)VERIFY_MAX * V * 4);
+    L.vgather = take((size_t)VERIFY_MAX * V * 4);
+    L.vnext = take(VERIFY_MAX * 4);
     L.total = off;
 }
 
@@ -150,6 +156,7 @@ struct edgefm_model {
     // pinned staging
     int32_t *pin_tok;  // [max_seq_len]
     float *pin_logits; // [vocab]
+    float *pin_vlogits; // [VERIFY_MAX][vocab], allocated by the first verify step that returns logits
     int32_t *pin_next; // [1]
     int n_part;        // lm_head partial count
     uint32_t n_subset; // candidate tokens of a pruned vocabulary (0 = the whole vocabulary)
@@ -285,6 +292,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     m->last_hip = 0;
     m->pin_tok = nullptr;
     m->pin_logits = nullptr;
+    m->pin_vlogits = nullptr;
     m->pin_next = nullptr;
     m->n_part = 0;
     Dims &D = m->D;
@@ -328,7 +336,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     LOADCHK(hipStreamCreateWithFlags(&m->cap_stream, hipStreamNonBlocking));
     LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_tok), (size_t)D.max_seq * 4, hipHostMallocDefault));
     LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_logits), (size_t)D.V * 4, hipHostMallocDefault));
-    LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_next), 64, hipHostMallocDefault));
+    LOADCHK(hipHostMalloc(reinterpret_cast<void **>(&m->pin_next), 64 + VERIFY_MAX * 4, hipHostMallocDefault));
 
     // copy the canonical tensors into the arena
     const size_t H = D.H, I = D.I, V = D.V, qd = D.qd(), R = D.R();
@@ -338,6 +346,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     LOADCHK(cp(m->L.embed, w->embed, V * H * 2));
     if (!cfg->tie_embeddings) LOADCHK(cp(m->L.lm_head, w->lm_head, V * H * 2));
     LOADCHK(cp(m->L.final_norm, w->final_norm, H * 2));
+    launch_convert_w16(D, m->lm(), m->at<uint16_t>(m->L.p_lm), V * H, m->stream);  // after the copies above, same stream
     m->LW.resize(D.L);
     m->PW.resize(D.L);
     for (int l = 0; l < D.L; ++l) {
@@ -424,20 +433,31 @@ void edgefm_model_free(edgefm_model *m) {
     if (m->cap_stream) (void)hipStreamDestroy(m->cap_stream);
     if (m->pin_tok) (void)hipHostFree(m->pin_tok);
     if (m->pin_logits) (void)hipHostFree(m->pin_logits);
+    if (m->pin_vlogits) (void)hipHostFree(m->pin_vlogits);
     if (m->pin_next) (void)hipHostFree(m->pin_next);
     delete m;
 }
 
-int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, const void *embeds_dev,
-                   uint32_t n_embeds, float *logits_host, int32_t *next_host) {
-    if (!m) return EDGEFM_ERR_INVALID_ARG;
+namespace {
+
+// Argument checks shared by prefill and the verify step.
+int check_append(const edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, const void *embeds_dev,
+                 uint32_t n_embeds) {
     const uint64_t n64 = (uint64_t)n_tokens + n_embeds;
     if (n64 == 0 || (n_tokens && !tok_host) || (n_embeds && !embeds_dev)) return EDGEFM_ERR_INVALID_ARG;
     if ((uint64_t)m->kv_len + n64 > m->cfg.max_seq_len) return EDGEFM_ERR_CONTEXT_OVERFLOW;
     for (uint32_t t = 0; t < n_tokens; ++t)
         if (tok_host[t] < 0 || (uint32_t)tok_host[t] >= m->cfg.vocab) return EDGEFM_ERR_BAD_TOKEN;
+    return EDGEFM_OK;
+}
+
+// Embed T = n_embeds + n_tokens new positions and run them through every layer (Eq. 3), appending their K/V at
+// positions kv_len ...  Leaves the residual stream of the new positions in X.  With last_row_only the last
+// layer's MLP runs on the last position alone (nothing else reads the others).
+int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, const void *embeds_dev, uint32_t n_embeds,
+                   bool last_row_only) {
     const Dims &D = m->D;
-    const int T = (int)n64, p0 = (int)m->kv_len, ctx = p0 + T, ctx_pad = (ctx + 63) / 64 * 64;
+    const int T = (int)(n_tokens + n_embeds), p0 = (int)m->kv_len, ctx = p0 + T, ctx_pad = (ctx + 63) / 64 * 64;
     hipStream_t st = m->stream;
     int *tok = m->at<int>(m->L.tok);
     if (n_tokens) {
@@ -464,7 +484,7 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
         launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
         launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, st);
         launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, st);
-        if (l == D.L - 1) {
+        if (l == D.L - 1 && last_row_only) {
             // Nothing reads the last layer's MLP output except the final norm of the last position (the
             // cache rows of every layer are complete at this point): one row through the decode kernels.
             float *xl = X + (size_t)(T - 1) * D.H, *h = m->at<float>(m->L.h);
@@ -476,8 +496,23 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
         launch_gemm(D, EPI_SWIGLU, Ahi, Alo, P.w_gate_up, T, D.I, D.H, nullptr, nullptr, Hhi, Hlo, ws, st);
         launch_gemm(D, EPI_RESID, Hhi, Hlo, P.w_down, T, D.H, D.I, nullptr, X, nullptr, nullptr, ws, st);
     }
+    return EDGEFM_OK;
+}
+
+}  // namespace
+
+int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, const void *embeds_dev,
+                   uint32_t n_embeds, float *logits_host, int32_t *next_host) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    int rc = check_append(m, tok_host, n_tokens, embeds_dev, n_embeds);
+    if (rc != EDGEFM_OK) return rc;
+    const Dims &D = m->D;
+    const int T = (int)(n_tokens + n_embeds), ctx = (int)m->kv_len + T;
+    hipStream_t st = m->stream;
+    rc = enqueue_layers(m, tok_host, n_tokens, embeds_dev, n_embeds, true);
+    if (rc != EDGEFM_OK) return rc;
     // only the last position needs logits: final norm + lm_head as a GEMV on that row
-    launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), X + (size_t)(T - 1) * D.H,
+    launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), m->at<float>(m->L.X) + (size_t)(T - 1) * D.H,
                   m->at<float>(m->L.logits), m->at<float>(m->L.hidden), m->at<float>(m->L.part_val),
                   m->at<int>(m->L.part_idx), &m->n_part, m->n_subset ? m->at<int>(m->L.subset) : nullptr, (int)m->n_subset, st);
     launch_finish(m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx), m->n_part, m->d_next(), m->d_token(),
@@ -487,6 +522,46 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     m->kv_len = (uint32_t)ctx;
     m->have_prev_token = true;
     return fetch_outputs(m, logits_host, next_host);
+}
+
+int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, float *logits_host,
+                       int32_t *next_host) {
+    if (!m) return EDGEFM_ERR_INVALID_ARG;
+    if (n_tokens == 0 || n_tokens > VERIFY_MAX) return EDGEFM_ERR_INVALID_ARG;
+    int rc = check_append(m, tok_host, n_tokens, nullptr, 0);
+    if (rc != EDGEFM_OK) return rc;
+    const Dims &D = m->D;
+    const int T = (int)n_tokens, ctx = (int)m->kv_len + T;
+    const size_t nl = n_logits(m);
+    if (logits_host && !m->pin_vlogits)
+        HIPCHK(m, hipHostMalloc(reinterpret_cast<void **>(&m->pin_vlogits), (size_t)VERIFY_MAX * D.V * 4, hipHostMallocDefault));
+    hipStream_t st = m->stream;
+    rc = enqueue_layers(m, tok_host, n_tokens, nullptr, 0, false);
+    if (rc != EDGEFM_OK) return rc;
+    // every new position needs its prediction: final norm and lm_head as a T-row GEMM against the f16 copy
+    uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo);
+    float *vlogits = m->at<float>(m->L.vlogits);
+    const int *subset = m->n_subset ? m->at<int>(m->L.subset) : nullptr;
+    launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);
+    launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
+                m->at<float>(m->L.gemm_ws), st);
+    launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
+    launch_set_int(m->d_pos(), ctx, st);
+    const float *src = vlogits;
+    if (logits_host && subset) {
+        launch_gather_logits(vlogits, T, D.V, subset, (int)m->n_subset, m->at<float>(m->L.vgather), st);
+        src = m->at<float>(m->L.vgather);
+    }
+    HIPCHK(m, hipGetLastError());
+    m->kv_len = (uint32_t)ctx;
+    m->have_prev_token = true;
+    if (logits_host) HIPCHK(m, hipMemcpyAsync(m->pin_vlogits, src, (size_t)T * nl * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(m, hipMemcpyAsync(m->pin_next + 16, m->at<int>(m->L.vnext), (size_t)T * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(m, hipStreamSynchronize(st));
+    HIPCHK(m, hipGetLastError());
+    if (logits_host) memcpy(logits_host, m->pin_vlogits, (size_t)T * nl * 4);
+    if (next_host) memcpy(next_host, m->pin_next + 16, (size_t)T * 4);
+    return EDGEFM_OK;
 }
 
 int edgefm_decode_step(edgefm_model *m, int32_t token, float *logits_host, int32_t *next_host) {
@@ -614,6 +689,25 @@ int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n) {
     HIPCHK(m, hipGetLastError());
     m->kv_len = n;
     m->have_prev_token = false;
+    return EDGEFM_OK;
+}
+
+int edgefm_debug_verify_hidden(edgefm_model *m, uint32_t row, float *hidden_host) {
+    if (!m || !hidden_host || row >= VERIFY_MAX) return EDGEFM_ERR_INVALID_ARG;
+    const size_t H = (size_t)m->D.H;
+    std::vector<uint16_t> hi(H), lo(H);
+    HIPCHK(m, hipStreamSynchronize(m->stream));
+    HIPCHK(m, hipMemcpy(hi.data(), m->at<uint16_t>(m->L.Ahi) + row * H, H * 2, hipMemcpyDeviceToHost));
+    HIPCHK(m, hipMemcpy(lo.data(), m->at<uint16_t>(m->L.Alo) + row * H, H * 2, hipMemcpyDeviceToHost));
+    auto f16 = [](uint16_t b) -> float {  // IEEE binary16 -> float
+        const uint32_t s = (uint32_t)(b & 0x8000u) << 16, e = (b >> 10) & 0x1fu, f = b & 0x3ffu;
+        if (e == 0) return (s ? -1.0f : 1.0f) * ldexpf((float)f, -24);
+        uint32_t u = e == 31 ? (s | 0x7f800000u | (f << 13)) : (s | ((e + 112u) << 23) | (f << 13));
+        float r;
+        memcpy(&r, &u, 4);
+        return r;
+    };
+    for (size_t i = 0; i < H; ++i) hidden_host[i] = f16(hi[i]) + f16(lo[i]);
     return EDGEFM_OK;
 }
 

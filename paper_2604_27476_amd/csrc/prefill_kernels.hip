@@ -887,6 +887,50 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Greedy choice for every row of a [T, V] logits matrix (lowest token id on ties), optionally over a list of
+// candidate ids.  One workgroup per row.  The last row's token also becomes the device-side current token.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_argmax_rows(const float *__restrict__ logits, int V, const int *__restrict__ subset, int n_subset,
+              int *__restrict__ next_rows, int *__restrict__ d_next, int *__restrict__ d_token) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    const float *row = logits + (size_t)blockIdx.x * V;
+    const int n = subset ? n_subset : V;
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    for (int i = threadIdx.x; i < n; i += 256) {  // ids are visited in increasing order per thread
+        const int id = subset ? subset[i] : i;
+        const float v = row[id];
+        if (v > best) { best = v; best_i = id; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float v = __shfl_xor(best, o, WAVE);
+        const int i = __shfl_xor(best_i, o, WAVE);
+        if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
+    }
+    if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = best_i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < best_i)) { best = bv[w]; best_i = bi[w]; }
+        if (best_i == 0x7fffffff) best_i = subset ? subset[0] : 0;  // all NaN/-inf: still a valid id
+        next_rows[blockIdx.x] = best_i;
+        if (blockIdx.x == gridDim.x - 1) { d_next[0] = best_i; d_token[0] = best_i; }
+    }
+}
+
+// out[t][i] = logits[t][subset[i]]: the candidates' logits in candidate order
+__global__ void __launch_bounds__(256)
+k_gather_logits(const float *__restrict__ logits, int V, const int *__restrict__ subset, int n_subset,
+                float *__restrict__ out) {
+    const float *row = logits + (size_t)blockIdx.y * V;
+    float *dst = out + (size_t)blockIdx.y * n_subset;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n_subset; i += gridDim.x * 256) dst[i] = row[subset[i]];
+}
+
 // ================================================================================================
 // launchers
 // ================================================================================================
@@ -1081,6 +1125,17 @@ void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const
     else
         hipLaunchKernelGGL((k_flash_attn<64>), grid, block, 0, st, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, D.nq,
                            D.g(), scale_log2e);
+}
+
+void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, int *next_rows, int *d_next,
+                        int *d_token, hipStream_t st) {
+    hipLaunchKernelGGL(k_argmax_rows, dim3(T), dim3(256), 0, st, logits, V, subset, n_subset, next_rows, d_next, d_token);
+}
+
+void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,
+                          hipStream_t st) {
+    const int bx = std::min(64, (n_subset + 255) / 256);
+    hipLaunchKernelGGL(k_gather_logits, dim3(bx, T), dim3(256), 0, st, logits, V, subset, n_subset, out);
 }
 
 }  // namespace efm

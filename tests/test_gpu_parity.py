@@ -360,6 +360,122 @@ def test_vocab_subset_at_7b_width():
     P.close()
 
 
+def _check_verify(P, tokens, where, subset=None):
+    """One verify step of the GPU model against the oracle's block forward over the same tokens."""
+    o = P.om.forward(np.asarray(tokens, np.int32), logits="all")
+    nxt, lg = P.gm.verify_step(tokens, want_logits=True)
+    for i in range(len(tokens)):
+        ol = o["logits"][i]
+        want = None
+        if subset is not None:
+            want, ol = oracle.restricted_argmax(ol, subset)
+        eh = rel_l2(P.gm.verify_hidden(i), o["hidden"][i])
+        el = rel_l2(lg[i], ol)
+        P.worst["hidden"] = max(P.worst["hidden"], eh); P.worst["logits"] = max(P.worst["logits"], el)
+        assert eh <= REL_TOL and el <= REL_TOL, f"{where} row {i}: hidden {eh:.2e} logits {el:.2e}"
+        if subset is None:
+            check_token(int(nxt[i]), ol, f"{where} row {i}")
+        else:
+            top = np.sort(ol)[-2:]
+            assert int(nxt[i]) in subset
+            if len(ol) == 1 or top[1] - top[0] > MARGIN:
+                assert int(nxt[i]) == want
+    return nxt
+
+
+def test_verify_step_equals_block_forward_and_decode_steps():
+    """edgefm_verify_step (Section 3.11, verification of a proposed block): predictions after every position of
+    the block against the oracle's block forward; KV rows of the block; equivalence with decode steps on the
+    GPU; roll-back of a rejected tail with kv_reset; candidate subsets."""
+    shape = TINY_BF16.with_(max_seq_len=160)
+    P = Pair(shape)
+    g, o = P.gm, P.om
+    prompt = synth.make_prompt(shape, 37)
+    rng = np.random.default_rng(3)
+    P.prefill(prompt)
+    pos = 37
+    for m in (1, 2, 5, 8, 32):
+        block = rng.integers(0, shape.vocab, size=m).astype(np.int32)
+        _check_verify(P, block, f"verify m={m}")
+        pos += m
+        assert g.kv_len == pos == o.kv_len
+    P.check_kv([0, 1], [36, 37, 40, pos - 1])
+    # a block from an empty context (positions 0..m-1)
+    g.kv_reset(0); o.kv_reset(0)
+    _check_verify(P, prompt[:9], "verify from empty")
+    # same predictions as explicit decode steps (different kernels), then chained decode from the last one
+    g.kv_reset(0)
+    g.prefill(prompt, want_logits=False)
+    block = rng.integers(0, shape.vocab, size=6).astype(np.int32)
+    nxt, lg = g.verify_step(block, want_logits=True)
+    hv = [g.verify_hidden(i).copy() for i in range(6)]
+    chained, _ = g.decode_step(-1)
+    g.kv_reset(37)
+    for i in range(6):
+        t, l1 = g.decode_step(int(block[i]), want_logits=True)
+        assert rel_l2(g.last_hidden(), hv[i]) <= 2e-4 and rel_l2(l1, lg[i]) <= 2e-4
+        top = np.sort(l1)[-2:]
+        if top[1] - top[0] > MARGIN:
+            assert t == int(nxt[i])
+    t7, _ = g.decode_step(int(nxt[5]))
+    assert t7 == chained
+    # speculative loop shape: propose a block, verify it, keep the agreeing prefix, drop the rest
+    g.kv_reset(36)
+    o.kv_reset(0)
+    o.forward(prompt[:36], logits="none", want_hidden=False)
+    truth, clear = [int(prompt[36])], True
+    for _ in range(5):
+        r = o.decode_step(truth[-1])
+        top = np.sort(r["logits"])[-2:]
+        clear = clear and (top[1] - top[0] > MARGIN)
+        truth.append(int(r["next"][0]))                  # the oracle's greedy continuation of the prompt
+    proposal = np.array(truth, np.int32)
+    proposal[4] = (proposal[4] + 1) % shape.vocab        # the draft goes wrong at its fifth token
+    nxt, _ = g.verify_step(proposal)
+    assert g.kv_len == 42
+    agree = 1
+    while agree < 6 and int(nxt[agree - 1]) == int(proposal[agree]):
+        agree += 1
+    assert agree <= 4                                    # the prediction after token 3 cannot be the corrupted token
+    if clear:
+        assert agree == 4 and int(nxt[3]) == truth[4]
+    g.kv_reset(36 + agree)                               # commit: the cache advances by what was accepted
+    assert g.kv_len == 36 + agree
+    t, _ = g.decode_step(int(nxt[agree - 1]))            # generation goes on from the base model's own token
+    if clear:
+        assert t == truth[5]
+    # candidate subsets
+    subset = np.sort(rng.choice(shape.vocab, size=211, replace=False)).astype(np.int32)
+    g.set_vocab_subset(subset)
+    g.kv_reset(0); o.kv_reset(0)
+    _check_verify(P, prompt[:7], "verify with subset", subset=subset)
+    g.set_vocab_subset(None)
+    E = binding.EdgefmError
+    for bad in (np.zeros(0, np.int32), np.zeros(33, np.int32)):
+        with pytest.raises(E):
+            g.verify_step(bad)
+    print(f"verify tiny worst {P.worst}")
+    P.close()
+
+
+def test_verify_step_7b_width_context_1000():
+    """The verify step at the 7B-shaped width (two layers) on top of a 1000-position context."""
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    P.om.kv_reset(0); P.gm.kv_reset(0)
+    ctx = 1000
+    rows = [synth.make_kv_rows(shape, l, ctx) for l in range(P.L)]
+    P.om.kv_inject(rows)
+    for l, (k, v) in enumerate(rows):
+        P.gm.kv_write(l, k, v)
+    P.gm.set_kv_len(ctx)
+    rng = np.random.default_rng(4)
+    for m in (4, 8):
+        _check_verify(P, rng.integers(0, shape.vocab, size=m).astype(np.int32), f"7b-width verify m={m}")
+    assert P.gm.kv_len == ctx + 12
+    print(f"verify 7b-width worst {P.worst}")
+
+
 # --------------------------------------------------------------------------------------------------
 # decode attention over long injected contexts (split-context path at its real sizes)
 # --------------------------------------------------------------------------------------------------
