@@ -120,14 +120,17 @@ void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float 
 // Kf[kvh][j][i] <- K[l][kvh][j][i];  Vt[kvh][i][.] <- V[l][kvh][j][i], keys permuted within groups of 16
 void launch_prep_kv(const Dims &D, const uint16_t *kcache_l, const uint16_t *vcache_l, int ctx, int ctx_pad,
                     uint16_t *Kf, uint16_t *Vt, hipStream_t st);
-// causal GQA flash attention for queries p0..p0+T-1 over keys 0..p0+t; output as an f16 pair
+// causal GQA flash attention for queries p0..p0+T-1 over keys 0..p0+t; output as an f16 pair.
+// part: scratch for key-split partial records, FLASH_PART_RECORDS x 128 x (d + 2) floats (null: never split)
+constexpr size_t FLASH_PART_RECORDS = 2048;
 void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *Kf, const uint16_t *Vt,
-                       int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st);
+                       int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, float *part, hipStream_t st);
 
 // next_rows[t] <- argmax_i logits[t][i] over the vocabulary or the candidate ids (lowest id on ties);
 // d_next, d_token <- next_rows[T-1]
-void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, int *next_rows, int *d_next,
-                        int *d_token, hipStream_t st);
+// (part_val, part_idx: scratch for 32 T partials)
+void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, float *part_val,
+                        int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st);
 // out[t][i] <- logits[t][subset[i]]
 void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,
                           hipStream_t st);

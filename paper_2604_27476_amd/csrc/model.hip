@@ -31,6 +31,7 @@ struct Layout {
     // prefill scratch
     size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Kf, Vt, tok, gemm_ws;
     size_t subset;  // [vocab] int32: candidate token ids of a pruned vocabulary
+    size_t flash_part;  // key-split partial records of the prefill attention
     size_t p_lm, vlogits, vgather, vnext;  // verify step: f16 copy of lm_head, [32][vocab] logits (raw, gathered), tokens
     size_t total;
 };
@@ -38,6 +39,7 @@ struct Layout {
 constexpr int ATTN_SPLITS = 64;
 constexpr int MAX_PARTIALS = 4096;
 constexpr uint32_t VERIFY_MAX = 32;  // positions per verify step (sizes its logits buffers)
+static_assert(VERIFY_MAX * 32 <= MAX_PARTIALS, "row-argmax partials share the lm_head partial buffers");
 
 struct Sizes {
     size_t layer_kv;  // elements of one layer of K (or V)
@@ -128,6 +130,7 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.tok = take(Tm * 4);
     L.gemm_ws = take(GEMM_WS_BYTES);
     L.subset = take(V * 4);
+    L.flash_part = take(FLASH_PART_RECORDS * 128 * (d + 2) * 4);
     L.p_lm = take(V * H * 2);
     L.vlogits = take((size_t)VERIFY_MAX * V * 4);
     L.vgather = take((size_t)VERIFY_MAX * V * 4);
@@ -482,7 +485,7 @@ int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
                     nullptr, ws, st);
         launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, m->kc(l), m->vc(l), st);
         launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
-        launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, st);
+        launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, m->at<float>(m->L.flash_part), st);
         launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, st);
         if (l == D.L - 1 && last_row_only) {
             // Nothing reads the last layer's MLP output except the final norm of the last position (the
@@ -545,7 +548,8 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
     launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);
     launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
                 m->at<float>(m->L.gemm_ws), st);
-    launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
+    launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx),
+                       m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
     launch_set_int(m->d_pos(), ctx, st);
     const float *src = vlogits;
     if (logits_host && subset) {

@@ -732,7 +732,7 @@ template <int D>
 __global__ void __launch_bounds__(256, 2)
 k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *__restrict__ Kf,
              const uint16_t *__restrict__ Vt, int ctx_pad, int T, int p0, uint16_t *__restrict__ Ohi,
-             uint16_t *__restrict__ Olo, int nq, int g, float scale_log2e) {
+             uint16_t *__restrict__ Olo, int nq, int g, float scale_log2e, int n_splits, float *__restrict__ part) {
     constexpr int NKS = D / 16;        // MFMA k-steps over the head dimension
     constexpr int NDB = D / 32;        // 32-row blocks of O^T
     constexpr int KROW = D * 2;        // bytes of a K tile row
@@ -746,7 +746,9 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int fr = lane & 31, hf = lane >> 5, sw = fr & 7;
     const int nqb = (T + 127) / 128;
-    const int qb = nqb - 1 - (int)blockIdx.x / nq, h = (int)blockIdx.x % nq, kvh = h / g;
+    // work unit = (query block, head, key split); heaviest query blocks first
+    const int unit = (int)blockIdx.x / n_splits, split = (int)blockIdx.x % n_splits;
+    const int qb = nqb - 1 - unit / nq, h = unit % nq, kvh = h / g;
     const int qb0 = qb * 128;
     const int tq = qb0 + wave * 32 + fr;  // this lane's query (index into the new block)
     const int qd = nq * D;
@@ -791,18 +793,22 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
 
     const int last_q = min(T, qb0 + 128) - 1;    // last query of the workgroup
     const int n_tiles = (p0 + last_q) / 64 + 1;  // key tiles 0 .. n_tiles-1 hold keys <= p0 + last_q
+    // this workgroup's share of them: tiles [kt0, kt1) (with n_splits > 1 the shares meet in k_flash_merge)
+    const int tps = (n_tiles + n_splits - 1) / n_splits;
+    const int kt0 = split * tps, kt1 = min(n_tiles, kt0 + tps);
+    if (kt0 >= kt1) return;
     const int wave_first_pos = p0 + qb0 + wave * 32;
     const int wave_last_key = p0 + min(T - 1, qb0 + wave * 32 + 31);
     const int qpos = p0 + tq;
 
-    issue(0);
-    for (int kt = 0; kt < n_tiles; ++kt) {
+    issue(kt0);
+    for (int kt = kt0; kt < kt1; ++kt) {
         const int key0 = kt * 64;
         // this wave's part of tile kt has landed; after the barrier every part has, and every wave is done with
         // the other stage (tile kt-1), which then receives tile kt+1
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (kt + 1 < n_tiles) issue(kt + 1);
+        if (kt + 1 < kt1) issue(kt + 1);
         if (key0 > wave_last_key) continue;  // tile entirely above this wave's diagonal (wave-uniform)
         const uint8_t *sK = stages + (kt & 1) * STAGE, *sV = sK + TILE_K;
 
@@ -870,6 +876,24 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
         }
     }
     const float ltot = lrow + __shfl_xor(lrow, 32, WAVE);
+    if (n_splits > 1) {
+        // partial record of (unit, split): m[128], l[128], then O^T as [D/4][128][4] floats (unnormalised)
+        float *rec = part + (size_t)(unit * n_splits + split) * (128 * (D + 2));
+        const int q = wave * 32 + fr;
+        if (hf == 0) {
+            rec[q] = mrow;
+            rec[128 + q] = ltot;
+        }
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int dg = db * 8 + 2 * i4 + hf;  // dims 4 dg .. 4 dg + 3
+                *reinterpret_cast<f32x4 *>(rec + 256 + ((size_t)dg * 128 + q) * 4) =
+                    f32x4{oacc[db][4 * i4 + 0], oacc[db][4 * i4 + 1], oacc[db][4 * i4 + 2], oacc[db][4 * i4 + 3]};
+            }
+        return;
+    }
     if (tq < T) {
         const float inv = 1.0f / ltot;
         uint16_t *oh = Ohi + (size_t)tq * qd + h * D, *ol = Olo + (size_t)tq * qd + h * D;
@@ -887,20 +911,66 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
     }
 }
 
+// Combine the key splits of k_flash_attn: O = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s, in split
+// order.  Grid (query block x head, D / 8); thread = (query, one group of four output dimensions), so that all of
+// a thread's loads are in flight together.
+template <int D>
+__global__ void __launch_bounds__(256)
+k_flash_merge(const float *__restrict__ part, int n_splits, int T, int p0, uint16_t *__restrict__ Ohi,
+              uint16_t *__restrict__ Olo, int nq) {
+    const int nqb = (T + 127) / 128;
+    const int unit = blockIdx.x, qb = nqb - 1 - unit / nq, h = unit % nq;
+    const int q = threadIdx.x & 127, half = threadIdx.x >> 7;
+    const int tq = qb * 128 + q;
+    if (tq >= T) return;
+    const int last_q = min(T, qb * 128 + 128) - 1, n_tiles = (p0 + last_q) / 64 + 1;
+    const int tps = (n_tiles + n_splits - 1) / n_splits, used = (n_tiles + tps - 1) / tps;  // splits that had tiles
+    const float *rec0 = part + (size_t)unit * n_splits * (128 * (D + 2));
+    float M = -1.0e30f;
+    for (int sp = 0; sp < used; ++sp) M = fmaxf(M, rec0[(size_t)sp * (128 * (D + 2)) + q]);
+    float w[8], l = 0.f;  // n_splits <= 8
+#pragma unroll
+    for (int sp = 0; sp < 8; ++sp) {
+        w[sp] = 0.f;
+        if (sp < used) {
+            const float *rec = rec0 + (size_t)sp * (128 * (D + 2));
+            w[sp] = __builtin_amdgcn_exp2f(rec[q] - M);
+            l += rec[128 + q] * w[sp];
+        }
+    }
+    const float inv = 1.0f / l;
+    const int qd = nq * D;
+    uint16_t *oh = Ohi + (size_t)tq * qd + h * D, *ol = Olo + (size_t)tq * qd + h * D;
+    {
+        const int dg = blockIdx.y * 2 + half;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp)
+            if (sp < used)
+                acc += *reinterpret_cast<const f32x4 *>(rec0 + (size_t)sp * (128 * (D + 2)) + 256 + ((size_t)dg * 128 + q) * 4) * w[sp];
+        const HiLo s0 = split2_f16(acc[0] * inv, acc[1] * inv), s1 = split2_f16(acc[2] * inv, acc[3] * inv);
+        *reinterpret_cast<u32x2 *>(oh + 4 * dg) = u32x2{s0.hi, s1.hi};
+        *reinterpret_cast<u32x2 *>(ol + 4 * dg) = u32x2{s0.lo, s1.lo};
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Greedy choice for every row of a [T, V] logits matrix (lowest token id on ties), optionally over a list of
-// candidate ids.  One workgroup per row.  The last row's token also becomes the device-side current token.
+// candidate ids.  Two steps: ARGMAX_CHUNKS workgroups per row leave (max, id) partials, one more kernel picks
+// among them and makes the last row's token the device-side current token.
 // ------------------------------------------------------------------------------------------------
+constexpr int ARGMAX_CHUNKS = 32;
 __global__ void __launch_bounds__(256)
 k_argmax_rows(const float *__restrict__ logits, int V, const int *__restrict__ subset, int n_subset,
-              int *__restrict__ next_rows, int *__restrict__ d_next, int *__restrict__ d_token) {
+              float *__restrict__ part_val, int *__restrict__ part_idx) {
     __shared__ float bv[4];
     __shared__ int bi[4];
-    const float *row = logits + (size_t)blockIdx.x * V;
+    const float *row = logits + (size_t)blockIdx.y * V;
     const int n = subset ? n_subset : V;
+    const int per = (n + ARGMAX_CHUNKS - 1) / ARGMAX_CHUNKS, beg = blockIdx.x * per, end = min(n, beg + per);
     float best = -INFINITY;
     int best_i = 0x7fffffff;
-    for (int i = threadIdx.x; i < n; i += 256) {  // ids are visited in increasing order per thread
+    for (int i = beg + threadIdx.x; i < end; i += 256) {  // ids are visited in increasing order per thread
         const int id = subset ? subset[i] : i;
         const float v = row[id];
         if (v > best) { best = v; best_i = id; }
@@ -916,10 +986,26 @@ k_argmax_rows(const float *__restrict__ logits, int V, const int *__restrict__ s
     if (threadIdx.x == 0) {
         for (int w = 1; w < 4; ++w)
             if (bv[w] > best || (bv[w] == best && bi[w] < best_i)) { best = bv[w]; best_i = bi[w]; }
-        if (best_i == 0x7fffffff) best_i = subset ? subset[0] : 0;  // all NaN/-inf: still a valid id
-        next_rows[blockIdx.x] = best_i;
-        if (blockIdx.x == gridDim.x - 1) { d_next[0] = best_i; d_token[0] = best_i; }
+        part_val[blockIdx.y * ARGMAX_CHUNKS + blockIdx.x] = best;
+        part_idx[blockIdx.y * ARGMAX_CHUNKS + blockIdx.x] = best_i;
     }
+}
+__global__ void __launch_bounds__(64)
+k_argmax_rows_finish(const float *__restrict__ part_val, const int *__restrict__ part_idx, int T,
+                     const int *__restrict__ subset, int *__restrict__ next_rows, int *__restrict__ d_next,
+                     int *__restrict__ d_token) {
+    const int t = blockIdx.x * 64 + threadIdx.x;
+    if (t >= T) return;
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    for (int c = 0; c < ARGMAX_CHUNKS; ++c) {
+        const float v = part_val[t * ARGMAX_CHUNKS + c];
+        const int i = part_idx[t * ARGMAX_CHUNKS + c];
+        if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
+    }
+    if (best_i == 0x7fffffff) best_i = subset ? subset[0] : 0;  // all NaN/-inf: still a valid id
+    next_rows[t] = best_i;
+    if (t == T - 1) { d_next[0] = best_i; d_token[0] = best_i; }
 }
 
 // out[t][i] = logits[t][subset[i]]: the candidates' logits in candidate order
@@ -1116,20 +1202,34 @@ void launch_prep_kv(const Dims &D, const uint16_t *kc, const uint16_t *vc, int c
 }
 
 void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const uint16_t *Kf, const uint16_t *Vt,
-                       int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, hipStream_t st) {
-    const dim3 grid(((T + 127) / 128) * D.nq), block(256);
+                       int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, float *part, hipStream_t st) {
+    const int nqb = (T + 127) / 128, units = nqb * D.nq;
+    // Few (query block, head) units leave CUs idle and make the last block's key loop the whole duration: cut
+    // the key range so that about two workgroups per CU exist (at most 8 splits, at most the tile count, and
+    // within the records the scratch holds).
+    const int max_tiles = (p0 + T - 1) / 64 + 1;
+    int n_splits = part ? std::min(std::min(8, max_tiles), std::max(1, 512 / units)) : 1;
+    while (n_splits > 1 && (size_t)units * n_splits > FLASH_PART_RECORDS) --n_splits;
+    const dim3 grid(units * n_splits), block(256);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D.d);
-    if (D.d == 128)
+    if (D.d == 128) {
         hipLaunchKernelGGL((k_flash_attn<128>), grid, block, 0, st, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, D.nq,
-                           D.g(), scale_log2e);
-    else
+                           D.g(), scale_log2e, n_splits, part);
+        if (n_splits > 1)
+            hipLaunchKernelGGL((k_flash_merge<128>), dim3(units, 128 / 8), block, 0, st, part, n_splits, T, p0, Ohi, Olo, D.nq);
+    } else {
         hipLaunchKernelGGL((k_flash_attn<64>), grid, block, 0, st, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, D.nq,
-                           D.g(), scale_log2e);
+                           D.g(), scale_log2e, n_splits, part);
+        if (n_splits > 1)
+            hipLaunchKernelGGL((k_flash_merge<64>), dim3(units, 64 / 8), block, 0, st, part, n_splits, T, p0, Ohi, Olo, D.nq);
+    }
 }
 
-void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, int *next_rows, int *d_next,
-                        int *d_token, hipStream_t st) {
-    hipLaunchKernelGGL(k_argmax_rows, dim3(T), dim3(256), 0, st, logits, V, subset, n_subset, next_rows, d_next, d_token);
+void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, float *part_val,
+                        int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st) {
+    hipLaunchKernelGGL(k_argmax_rows, dim3(ARGMAX_CHUNKS, T), dim3(256), 0, st, logits, V, subset, n_subset, part_val, part_idx);
+    hipLaunchKernelGGL(k_argmax_rows_finish, dim3((T + 63) / 64), dim3(64), 0, st, part_val, part_idx, T, subset, next_rows,
+                       d_next, d_token);
 }
 
 void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,
