@@ -46,12 +46,19 @@ struct MegaSync {
     unsigned n_wg;
 };
 
-// All workgroups have arrived and their earlier agent-scope stores are complete.
-__device__ __forceinline__ void grid_barrier(MegaSync &sy) {
+// Grid barrier in two halves, so that loads which do not depend on other workgroups (the next stage's weights)
+// can be issued between them: the release fence of the arrival then waits for this stage's stores only, not
+// for those loads.
+// arrive: this workgroup's agent-scope stores are complete and counted.
+__device__ __forceinline__ void grid_arrive(MegaSync &sy) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // each thread waits for its own stores
     __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(sy.ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// wait: every workgroup has arrived.  Thread 0 spins; its wave issues no weight prefetch, so the counter reads
+// do not queue behind one (vector-memory returns are in order per wave).
+__device__ __forceinline__ void grid_wait(MegaSync &sy) {
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(sy.ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (aload(sy.err) == 0) {
             int spins = 0;
             while (aload(sy.ctr) < sy.next) {
@@ -68,6 +75,10 @@ __device__ __forceinline__ void grid_barrier(MegaSync &sy) {
     }
     sy.next += sy.n_wg;
     __syncthreads();
+}
+__device__ __forceinline__ void grid_barrier(MegaSync &sy) {
+    grid_arrive(sy);
+    grid_wait(sy);
 }
 
 // Stage a vector that other workgroups produced (agent-scope loads), optionally RMSNorm * gain, into the
@@ -356,8 +367,9 @@ __device__ __forceinline__ void unit_rows(const MegaStage &s, int u, const uint1
 
 // Issue the loads of this wave's first pass of stage s (units gw and gw + gstride).  The loads are
 // predicated per lane (a wave without a unit passes nvec = 0), never skipped by a branch.
-__device__ __forceinline__ void stage_prefetch(Chunk4 &pre, const MegaStage &s, int gw, int gstride, int lane) {
-    const bool va = gw < s.n_units, vb = gw + gstride < s.n_units;
+__device__ __forceinline__ void stage_prefetch(Chunk4 &pre, const MegaStage &s, int gw, int gstride, int lane,
+                                               bool enabled) {
+    const bool va = enabled && gw < s.n_units, vb = enabled && gw + gstride < s.n_units;
     const uint16_t *rows[4];
     unit_rows(s, va ? gw : 0, rows[0], rows[1]);
     unit_rows(s, vb ? gw + gstride : (va ? gw : 0), rows[2], rows[3]);
@@ -408,31 +420,42 @@ k_decode_mega(const MegaArgs a) {
         if (tracing) a.trace[4 * st + k] = wall_clock64();
     };
     Chunk4 pre;
+    // Every stage ends with: arrive at the grid barrier (this stage's stores are complete), THEN issue the loads of
+    // the next GEMV stage's first pass, and the next stage begins with the wait half of the barrier: the weight
+    // stream goes on while the workgroups meet.  Wave 0 holds the thread that spins on the arrival counter and
+    // therefore never prefetches.
+    const bool pf_wave = wave != 0;
+    bool have_pre = false;  // `pre` holds this wave's first pass of the coming GEMV stage
     // The loop starts one stage early (st = -1 only prefetches stage 0): the chunk registers then have no
     // definition outside the loop, which keeps the compiler from holding two copies of them.
     for (int st = -1; st < a.n_stages; ++st) {
         const MegaStage d = load_stage(a.stages + (st < 0 ? 0 : st));
         if (st < 0) {
-            stage_prefetch(pre, d, gw, gstride, lane);
+            stage_prefetch(pre, d, gw, gstride, lane, pf_wave);
+            have_pre = pf_wave;
             continue;
         }
         stamp(st, 0);
         if (d.epi == MEPI_ATTN) {
             // Workgroups without an attention slice already stream their first O-projection pass; the others
             // issue it after the attention (the chunk registers are free during it).
-            grid_barrier(sy);
+            grid_wait(sy);
             stamp(st, 1);
             if (attn_wg) {
                 const int kvh = (int)blockIdx.x % a.nkv, s = (int)blockIdx.x / a.nkv;
                 mega_attention<KDT, D, GQ>(a, d.layer, pos, kvh, s, n_active, chunk, reinterpret_cast<float *>(smem), qs,
                                            knew, vnew, sm, sl, &ticket_s);
-                stage_prefetch(pre, load_stage(a.stages + st + 1), gw, gstride, lane);
+            }
+            grid_arrive(sy);
+            if (attn_wg) {
+                stage_prefetch(pre, load_stage(a.stages + st + 1), gw, gstride, lane, pf_wave);
+                have_pre = pf_wave;
             }
             stamp(st, 3);
             continue;
         }
         // ---- inputs of this stage are complete; stage its activation vector in LDS ----
-        if (st > 0) grid_barrier(sy);
+        if (st > 0) grid_wait(sy);
         stamp(st, 1);
         const int nvec = d.K >> 3;
         if (d.vec_kind == MVEC_EMBED) {
@@ -471,8 +494,9 @@ k_decode_mega(const MegaArgs a) {
             stage_shared_vec<WDT, false, true>(d.vec, nullptr, d.K, 0.f, smem, red, nullptr);
         }
         stamp(st, 2);
-        // ---- the wave's units, two per pass; the first pass was prefetched ----
-        bool first = true;
+        // ---- the wave's units, two per pass; the first pass was prefetched (not by wave 0) ----
+        bool first = have_pre;
+        have_pre = false;
         for (int ua = gw; ua < d.n_units; ua += 2 * gstride) {
             const int ub = ua + gstride;
             const bool vb = ub < d.n_units;
@@ -523,11 +547,17 @@ k_decode_mega(const MegaArgs a) {
             }
         }
         stamp(st, 3);
-        // ---- weights never depend on activations: start the next GEMV stage's first pass now ----
+        // ---- publish, then (weights never depend on activations) start the next GEMV stage's first pass ----
         if (st + 1 < a.n_stages) {
+            grid_arrive(sy);
             const MegaStage nx = load_stage(a.stages + st + 1);
-            if (nx.epi != MEPI_ATTN) stage_prefetch(pre, nx, gw, gstride, lane);
-            else if (!attn_wg) stage_prefetch(pre, load_stage(a.stages + st + 2), gw, gstride, lane);
+            if (nx.epi != MEPI_ATTN) {
+                stage_prefetch(pre, nx, gw, gstride, lane, pf_wave);
+                have_pre = pf_wave;
+            } else if (!attn_wg) {
+                stage_prefetch(pre, load_stage(a.stages + st + 2), gw, gstride, lane, pf_wave);
+                have_pre = pf_wave;
+            }
         }
     }
     // ---------------- greedy argmax over the lm_head partials ----------------------------------------
