@@ -1168,7 +1168,9 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
     // 128-row tiles where 256-row tiles would be at least half empty in their last row of tiles (they cost
     // about a tenth more per row, so long prompts stay with 256).  Mixing the two shapes in one GEMM (256-row
     // body, 128-row tail, separate launches) measured slower: neither launch fills the machine.
-    const bool rows128 = T < 1024 && (T - 1) % 256 < 128;
+    // ... or, for prompts below 1024, would not even give every CU one tile.
+    const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
+    const bool rows128 = T < 1024 && ((T - 1) % 256 < 128 || ((T + 255) / 256) * n_nt < std::min(device_cu_count(), 256));
     gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, rows128, st);
 }
 
