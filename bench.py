@@ -105,7 +105,7 @@ def sweep(args) -> int:
         # verify step of speculative decoding: m proposed tokens in one pass on top of the same context
         gm.kv_reset(0)
         gm.prefill(prompt, want_logits=False)
-        for mm in (2, 4, 8, 16, 32):
+        for mm in (1, 2, 3, 4, 8, 16, 32):
             block = synth.make_prompt(shape, mm, seed=27481)
             ts = []
             for _ in range(6):

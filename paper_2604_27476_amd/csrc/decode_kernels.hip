@@ -10,42 +10,6 @@
 namespace efm {
 
 // ------------------------------------------------------------------------------------------------
-// Activation vector staged in LDS.  Layout: two float4 arrays of nvec = n/8 entries,
-//   lo[v] = x[8v .. 8v+3], hi[v] = x[8v+4 .. 8v+7],
-// so that lane i of a wave reads lo[v0+i] / hi[v0+i]: consecutive 16-byte words, no bank conflicts.
-// With NORM the staged vector is RMSNorm(x) * gain.
-// ------------------------------------------------------------------------------------------------
-template <int DT, bool NORM>
-__device__ __forceinline__ void stage_vec(const float *__restrict__ x, const uint16_t *__restrict__ gain, int n,
-                                          float eps, float4 *xs, float *red) {
-    const int nvec = n >> 3;
-    float rstd = 1.f;
-    if constexpr (NORM) {
-        float ss = 0.f;
-        for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
-            const float4 a = reinterpret_cast<const float4 *>(x)[2 * v];
-            const float4 b = reinterpret_cast<const float4 *>(x)[2 * v + 1];
-            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
-        }
-        ss = block_sum(ss, red);
-        rstd = 1.0f / sqrtf(ss / (float)n + eps);
-    }
-    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
-        float4 a = reinterpret_cast<const float4 *>(x)[2 * v];
-        float4 b = reinterpret_cast<const float4 *>(x)[2 * v + 1];
-        if constexpr (NORM) {
-            float g[8];
-            unpack8<DT>(ld16(gain + 8 * v), g);
-            a.x = a.x * rstd * g[0]; a.y = a.y * rstd * g[1]; a.z = a.z * rstd * g[2]; a.w = a.w * rstd * g[3];
-            b.x = b.x * rstd * g[4]; b.y = b.y * rstd * g[5]; b.z = b.z * rstd * g[6]; b.w = b.w * rstd * g[7];
-        }
-        xs[v] = a;
-        xs[nvec + v] = b;
-    }
-    __syncthreads();
-}
-
-// ------------------------------------------------------------------------------------------------
 // embed: x <- upcast(E[token])
 // ------------------------------------------------------------------------------------------------
 template <int DT>
@@ -314,7 +278,13 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
     __shared__ uint32_t ticket_s;
 
     const int kvh = blockIdx.y, s = blockIdx.x;
-    const int n_keys = d_pos[0] + 1;
+    // query blockIdx.z of a block of positions (verify step): one position further, its own q / o / records
+    const int zq = blockIdx.z;
+    const int n_keys = d_pos[0] + 1 + zq;
+    q += (size_t)zq * gridDim.y * GQ * D;
+    o += (size_t)zq * gridDim.y * GQ * D;
+    part += (size_t)zq * gridDim.y * GQ * S * (D + 4);
+    counters += zq * gridDim.y;
     int chunk = (n_keys + S - 1) / S;
     if (chunk < ATTN_CHUNK_MIN) chunk = ATTN_CHUNK_MIN;
     const int n_active = (n_keys + chunk - 1) / chunk;
@@ -323,7 +293,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         // the spare workgroups pull the matrix of the next kernel (W_o) into L2 meanwhile: one word of every
         // 128-byte line of the slices that the GEMV workgroups b = r, r + 8, ... will stream, r being this
         // workgroup's XCD (workgroups go to the XCDs round-robin by linear index, and gridDim.x is a multiple of 8).
-        if (warm.base) {
+        if (warm.base && zq == 0) {
             const int r = s & 7;
             const int first = n_active + ((r - n_active) & 7);  // first spare slice index on XCD r
             if (first < S) {
@@ -633,8 +603,8 @@ void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st) {
 template <int KDT, int DD>
 static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
                           const int *d_pos, float *part, uint32_t *counters, float *o, const WarmJob &warm,
-                          hipStream_t st) {
-    const dim3 grid(G.attn_splits, D.nkv), block(256);
+                          int n_queries, hipStream_t st) {
+    const dim3 grid(G.attn_splits, D.nkv, n_queries), block(256);
     const float scale = 1.0f / sqrtf((float)D.d);
 #define ATTN_CASE(GQ)                                                                                          \
     case GQ:                                                                                                   \
@@ -650,7 +620,7 @@ static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uin
 
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
                         const int *d_pos, float *part, uint32_t *counters, float *o, const uint16_t *warm_w,
-                        hipStream_t st) {
+                        int n_queries, hipStream_t st) {
     WarmJob warm = {nullptr, 0, 0, 0};
     static const bool warm_on = !(getenv("EDGEFM_WARM") && getenv("EDGEFM_WARM")[0] == '0');
     // worthwhile only where the matrix fits the L2s (4 MB per XCD) with room to spare, and the slices map to XCDs
@@ -662,11 +632,11 @@ void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint1
         warm.n_wg = g.blocks;
     }
     if (D.kvdt == DT_BF16) {
-        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
-        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
+        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
+        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
     } else {
-        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
-        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, st);
+        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
+        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
     }
 }
 

@@ -1,0 +1,306 @@
+// Decode-step kernels for M positions at once (M <= 4): the verification pass of speculative decoding
+// (Section 3.11) as GEMVs.  Same structure as the single-position kernels of decode_kernels.hip -- every linear
+// layer streams its weights once with 128-bit loads, normalisation / bias / RoPE / cache write / SwiGLU /
+// residual adds live in prologues and epilogues -- but each weight vector is multiplied into M staged
+// activation vectors, so M positions cost one pass over the weights.  Position m of the block sits at
+// context position pos + m; its attention (launch_attn_decode with n_queries = M) sees keys 0 .. pos + m.
+#include "common.h"
+#include "gemv.h"
+#include "kernels.h"
+
+namespace efm {
+
+constexpr size_t MULTI_LDS_BYTES = 150 * 1024;  // dynamic LDS the kernels below may ask for
+
+// x[m] <- upcast(E[tok[m]]); grid (blocks, M)
+template <int DT>
+__global__ void k_embed_m(const uint16_t *__restrict__ E, const int *__restrict__ tok, float *__restrict__ x, int H) {
+    const uint16_t *row = E + (size_t)tok[blockIdx.y] * H;
+    float *dst = x + (size_t)blockIdx.y * H;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < H; i += gridDim.x * blockDim.x) dst[i] = up1<DT>(row[i]);
+}
+
+// fused QKV for M positions: RMSNorm prologue per position, GEMV, bias + RoPE at pos + m + cache write epilogue.
+// Work unit = the rotation partners (i, i + d/2) of one head, as in k_qkv.  q is [M][n_q d].
+template <int DT, int KDT, int M>
+__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const uint16_t *__restrict__ gain,
+        const float *__restrict__ x, const float *__restrict__ rope_cos, const float *__restrict__ rope_sin,
+        const int *__restrict__ d_pos, float *__restrict__ q, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
+        int H, int nq, int nkv, int d, int max_seq, float eps) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int half = d >> 1, n_units = (nq + 2 * nkv) * half, nvec = H >> 3, qd = nq * d;
+    const int unit0 = blockIdx.x * nw + wave;
+    Chunk<2, 7> pre;
+    if (unit0 < n_units) {  // weights first: they do not depend on the activations
+        const int hh = unit0 / half, r0 = hh * d + (unit0 - hh * half);
+        const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)(r0 + half) * H};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+#pragma unroll 1
+    for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+    const int pos = d_pos[0];
+    for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
+        const int hh = unit / half, i = unit - hh * half;
+        const int r0 = hh * d + i, r1 = r0 + half;
+        const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)r1 * H};
+        float acc[M][2];
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[m][0] = acc[m][1] = 0.f;
+        wave_dots_m<DT, 2, 7, M>(rows, smem, 0, nvec, lane, acc, pre, unit == unit0);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            float v0 = wave_sum(acc[m][0]), v1 = wave_sum(acc[m][1]);
+            if (lane != 0) continue;
+            const int p = pos + m;
+            if (bias) {
+                v0 += up1<DT>(bias[r0]);
+                v1 += up1<DT>(bias[r1]);
+            }
+            if (hh < nq + nkv) {
+                const float c = rope_cos[(size_t)p * half + i], s = rope_sin[(size_t)p * half + i];
+                const float y0 = v0 * c - v1 * s, y1 = v1 * c + v0 * s;
+                v0 = y0;
+                v1 = y1;
+            }
+            if (hh < nq) {
+                q[(size_t)m * qd + r0] = v0;
+                q[(size_t)m * qd + r1] = v1;
+            } else if (hh < nq + nkv) {
+                uint16_t *dst = kc + ((size_t)(hh - nq) * max_seq + p) * d;
+                dst[i] = down1<KDT>(v0);
+                dst[i + half] = down1<KDT>(v1);
+            } else {
+                uint16_t *dst = vc + ((size_t)(hh - nq - nkv) * max_seq + p) * d;
+                dst[i] = down1<KDT>(v0);
+                dst[i + half] = down1<KDT>(v1);
+            }
+        }
+    }
+}
+
+// x[m][r] += W[r] . vec[m] for M positions (O projection, down projection).  One pair of rows per wave (the
+// launcher sizes the grid so that no wave has a second pair).  When the M vectors do not fit LDS together
+// (down projection: M x 76 KB) they are staged in slices of slice_vec 16-byte words along K, and the wave keeps
+// its partial dot products in registers from slice to slice.
+template <int DT, int M>
+__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+k_gemv_resid_m(const uint16_t *__restrict__ W, const float *__restrict__ vec, float *__restrict__ x, int rows_n, int K,
+               int slice_vec) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int n_units = (rows_n + 1) >> 1, nvec = K >> 3;
+    const int unit = blockIdx.x * nw + wave;
+    const bool active = unit < n_units;
+    const int r0 = 2 * (active ? unit : 0), r1 = min(r0 + 1, rows_n - 1);
+    const uint16_t *rows[2] = {W + (size_t)r0 * K, W + (size_t)r1 * K};
+    Chunk<2, 7> pre;
+    if (active) chunk_load<2, 7>(pre, rows, lane, min(nvec, slice_vec));
+    float acc[M][2];
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[m][0] = acc[m][1] = 0.f;
+    for (int vbeg = 0; vbeg < nvec; vbeg += slice_vec) {
+        const int vend = min(nvec, vbeg + slice_vec), ns = vend - vbeg;
+        if (vbeg > 0) __syncthreads();  // every wave is done with the previous slice
+#pragma unroll 1
+        for (int m = 0; m < M; ++m)
+            stage_vec<DT, false>(vec + (size_t)m * K + (size_t)vbeg * 8, nullptr, ns * 8, 0.f, smem + 2 * ns * m, red);
+        if (active) wave_dots_m<DT, 2, 7, M>(rows, smem, vbeg, vend, lane, acc, pre, vbeg == 0);
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        const float o0 = wave_sum(acc[m][0]), o1 = wave_sum(acc[m][1]);
+        if (lane == 0 && active) {
+            x[(size_t)m * rows_n + r0] += o0;
+            if (r1 != r0) x[(size_t)m * rows_n + r1] += o1;
+        }
+    }
+}
+
+// h[m][j] = silu(W_gate[j] . RMSNorm(x[m])) * (W_up[j] . RMSNorm(x[m])); unit j = rows (j, I + j)
+template <int DT, int M>
+__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+k_gateup_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
+           float *__restrict__ h, int H, int I, float eps) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int nvec = H >> 3;
+    const int j0 = blockIdx.x * nw + wave;
+    Chunk<2, 7> pre;
+    if (j0 < I) {
+        const uint16_t *rows[2] = {W + (size_t)j0 * H, W + (size_t)(I + j0) * H};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+#pragma unroll 1
+    for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+    for (int j = j0; j < I; j += gridDim.x * nw) {
+        const uint16_t *rows[2] = {W + (size_t)j * H, W + (size_t)(I + j) * H};
+        float acc[M][2];
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[m][0] = acc[m][1] = 0.f;
+        wave_dots_m<DT, 2, 7, M>(rows, smem, 0, nvec, lane, acc, pre, j == j0);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const float g = wave_sum(acc[m][0]), u = wave_sum(acc[m][1]);
+            if (lane == 0) h[(size_t)m * I + j] = g / (1.0f + expf(-g)) * u;
+        }
+    }
+}
+
+// logits[m][i] = W_lm[token(i)] . RMSNorm(x[m]) for the n_rows candidate rows (the whole vocabulary, or the
+// ascending ids of `subset`); hidden[m] = RMSNorm(x[m]).  The greedy choice is left to launch_argmax_rows.
+template <int DT, int M>
+__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+k_lmhead_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
+           float *__restrict__ logits, float *__restrict__ hidden, int H, int n_rows, float eps,
+           const int *__restrict__ subset) {
+    extern __shared__ float4 smem[];
+    __shared__ float red[32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int nvec = H >> 3;
+    const int n_units = (n_rows + 1) >> 1;
+    const int unit0 = blockIdx.x * nw + wave;
+    auto token_of = [&](int i) { return subset ? subset[i] : i; };
+    Chunk<2, 7> pre;
+    if (unit0 < n_units) {
+        const uint16_t *rows[2] = {W + (size_t)token_of(2 * unit0) * H, W + (size_t)token_of(min(2 * unit0 + 1, n_rows - 1)) * H};
+        chunk_load<2, 7>(pre, rows, lane, nvec);
+    }
+#pragma unroll 1
+    for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+    if (blockIdx.x == 0) {  // export the final hidden states (the tensors the parity tolerance is stated on)
+        for (int m = 0; m < M; ++m)
+            for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+                reinterpret_cast<float4 *>(hidden + (size_t)m * H)[2 * v] = smem[2 * nvec * m + v];
+                reinterpret_cast<float4 *>(hidden + (size_t)m * H)[2 * v + 1] = smem[2 * nvec * m + nvec + v];
+            }
+    }
+    for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
+        const int r0 = 2 * unit, r1 = min(2 * unit + 1, n_rows - 1);
+        const uint16_t *rows[2] = {W + (size_t)token_of(r0) * H, W + (size_t)token_of(r1) * H};
+        float acc[M][2];
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[m][0] = acc[m][1] = 0.f;
+        wave_dots_m<DT, 2, 7, M>(rows, smem, 0, nvec, lane, acc, pre, unit == unit0);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const float o0 = wave_sum(acc[m][0]), o1 = wave_sum(acc[m][1]);
+            if (lane == 0) {
+                logits[(size_t)m * n_rows + r0] = o0;
+                if (r1 != r0) logits[(size_t)m * n_rows + r1] = o1;
+            }
+        }
+    }
+}
+
+// ================================================================================================
+// launchers
+// ================================================================================================
+namespace {
+
+struct Grid {
+    int blocks, threads;
+};
+// about one workgroup per CU, each wave owning whole units (same policy as the single-position kernels)
+Grid multi_grid(int n_units, int n_cu) {
+    const int per_cu = (n_units + n_cu - 1) / n_cu;
+    const int waves = per_cu < 4 ? 4 : (per_cu > 8 ? 8 : per_cu);
+    int blocks = (n_units + waves - 1) / waves;
+    if (blocks > n_cu) blocks = n_cu;
+    return {blocks, waves * 64};
+}
+
+#define DT_SWITCH(dt, ...)                          \
+    if ((dt) == DT_BF16) {                          \
+        constexpr int DT = DT_BF16;                 \
+        __VA_ARGS__                                 \
+    } else {                                        \
+        constexpr int DT = DT_F16;                  \
+        __VA_ARGS__                                 \
+    }
+#define M_SWITCH(m, ...)                                          \
+    switch (m) {                                                  \
+        case 1: { constexpr int M = 1; __VA_ARGS__ } break;       \
+        case 2: { constexpr int M = 2; __VA_ARGS__ } break;       \
+        case 3: { constexpr int M = 3; __VA_ARGS__ } break;       \
+        default: { constexpr int M = 4; __VA_ARGS__ } break;      \
+    }
+
+}  // namespace
+
+hipError_t multi_prepare() {
+    hipError_t e = hipSuccess;
+#define PREP(K)                                                                                                      \
+    if (e == hipSuccess)                                                                                             \
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize,       \
+                                (int)MULTI_LDS_BYTES);
+#define PREP_M(M)                                                                                                     \
+    PREP((k_qkv_m<DT_BF16, DT_BF16, M>)) PREP((k_qkv_m<DT_BF16, DT_F16, M>)) PREP((k_qkv_m<DT_F16, DT_BF16, M>))       \
+    PREP((k_qkv_m<DT_F16, DT_F16, M>)) PREP((k_gemv_resid_m<DT_BF16, M>)) PREP((k_gemv_resid_m<DT_F16, M>))           \
+    PREP((k_gateup_m<DT_BF16, M>)) PREP((k_gateup_m<DT_F16, M>)) PREP((k_lmhead_m<DT_BF16, M>))                       \
+    PREP((k_lmhead_m<DT_F16, M>))
+    PREP_M(1) PREP_M(2) PREP_M(3) PREP_M(4)
+#undef PREP_M
+#undef PREP
+    return e;
+}
+
+bool multi_supported(const Dims &D, const Geo &G, int M) {
+    if (M < 1 || M > MULTI_MAX) return false;
+    // the staged vectors of the QKV / gate-up / lm_head prologues have to fit LDS together ...
+    if ((size_t)M * D.H * 4 > MULTI_LDS_BYTES || (size_t)M * D.qd() * 4 > MULTI_LDS_BYTES) return false;
+    // ... and the residual GEMVs keep one pair of rows per wave
+    const Grid g = multi_grid((D.H + 1) / 2, G.n_cu);
+    return (size_t)g.blocks * (g.threads / 64) >= (size_t)(D.H + 1) / 2;
+}
+
+void launch_embed_m(const Dims &D, int M, const uint16_t *embed, const int *d_tok, float *x, hipStream_t st) {
+    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_embed_m<DT>, dim3((D.H + 255) / 256, M), dim3(256), 0, st, embed, d_tok, x, D.H);)
+}
+
+void launch_qkv_m(const Dims &D, const Geo &G, int M, const LayerW &W, const float *x, const float *rope_cos,
+                  const float *rope_sin, const int *d_pos, float *q, uint16_t *kc, uint16_t *vc, hipStream_t st) {
+    const size_t lds = (size_t)M * D.H * 4;
+    const Grid g = multi_grid((D.nq + 2 * D.nkv) * (D.d / 2), G.n_cu);
+    const uint16_t *bias = D.qkv_bias ? W.bqkv : nullptr;
+#define QKV_CALL(KDT)                                                                                                  \
+    M_SWITCH(M, hipLaunchKernelGGL((k_qkv_m<DT, KDT, M>), dim3(g.blocks), dim3(g.threads), lds, st, W.wqkv, bias,      \
+                                   W.attn_norm, x, rope_cos, rope_sin, d_pos, q, kc, vc, D.H, D.nq, D.nkv, D.d,       \
+                                   D.max_seq, D.eps);)
+    DT_SWITCH(D.wdt, if (D.kvdt == DT_BF16) { QKV_CALL(DT_BF16) } else { QKV_CALL(DT_F16) })
+#undef QKV_CALL
+}
+
+void launch_gemv_resid_m(const Dims &D, const Geo &G, int M, const uint16_t *W, int K, const float *vec, float *x,
+                         hipStream_t st) {
+    const int nvec = K / 8;
+    int slice_vec = (int)(MULTI_LDS_BYTES / ((size_t)M * 32));  // 16-byte words of each vector that fit together
+    slice_vec -= slice_vec % (64 * 7);                          // whole passes of a wave
+    if (slice_vec > nvec) slice_vec = nvec;
+    const size_t lds = (size_t)M * slice_vec * 32;
+    const Grid g = multi_grid((D.H + 1) / 2, G.n_cu);
+    DT_SWITCH(D.wdt, M_SWITCH(M, hipLaunchKernelGGL((k_gemv_resid_m<DT, M>), dim3(g.blocks), dim3(g.threads), lds, st, W,
+                                                    vec, x, D.H, K, slice_vec);))
+}
+
+void launch_gateup_m(const Dims &D, const Geo &G, int M, const LayerW &W, const float *x, float *h, hipStream_t st) {
+    const size_t lds = (size_t)M * D.H * 4;
+    const Grid g = multi_grid(D.I, G.n_cu);
+    DT_SWITCH(D.wdt, M_SWITCH(M, hipLaunchKernelGGL((k_gateup_m<DT, M>), dim3(g.blocks), dim3(g.threads), lds, st,
+                                                    W.w_gate_up, W.mlp_norm, x, h, D.H, D.I, D.eps);))
+}
+
+void launch_lmhead_m(const Dims &D, const Geo &G, int M, const uint16_t *lm, const uint16_t *final_norm, const float *x,
+                     float *logits, float *hidden, const int *subset, int n_subset, hipStream_t st) {
+    const size_t lds = (size_t)M * D.H * 4;
+    const int n_rows = subset ? n_subset : D.V;
+    const Grid g = multi_grid((n_rows + 1) / 2, G.n_cu);
+    DT_SWITCH(D.wdt, M_SWITCH(M, hipLaunchKernelGGL((k_lmhead_m<DT, M>), dim3(g.blocks), dim3(g.threads), lds, st, lm,
+                                                    final_norm, x, logits, hidden, D.H, n_rows, D.eps, subset);))
+}
+
+}  // namespace efm

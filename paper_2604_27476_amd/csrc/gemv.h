@@ -63,4 +63,86 @@ __device__ __forceinline__ void wave_dots(const uint16_t *const (&rows)[NR], con
     for (int r = 0; r < NR; ++r) out[r] = wave_sum(acc[r]);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Activation vector staged in LDS.  Layout: two float4 arrays of nvec = n/8 entries,
+//   lo[v] = x[8v .. 8v+3], hi[v] = x[8v+4 .. 8v+7],
+// so that lane i of a wave reads lo[v0+i] / hi[v0+i]: consecutive 16-byte words, no bank conflicts.
+// With NORM the staged vector is RMSNorm(x) * gain.
+// ------------------------------------------------------------------------------------------------
+template <int DT, bool NORM>
+__device__ __forceinline__ void stage_vec(const float *__restrict__ x, const uint16_t *__restrict__ gain, int n,
+                                          float eps, float4 *xs, float *red) {
+    const int nvec = n >> 3;
+    float rstd = 1.f;
+    if constexpr (NORM) {
+        float ss = 0.f;
+        for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+            const float4 a = reinterpret_cast<const float4 *>(x)[2 * v];
+            const float4 b = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+        }
+        ss = block_sum(ss, red);
+        rstd = 1.0f / sqrtf(ss / (float)n + eps);
+    }
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        float4 a = reinterpret_cast<const float4 *>(x)[2 * v];
+        float4 b = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+        if constexpr (NORM) {
+            float g[8];
+            unpack8<DT>(ld16(gain + 8 * v), g);
+            a.x = a.x * rstd * g[0]; a.y = a.y * rstd * g[1]; a.z = a.z * rstd * g[2]; a.w = a.w * rstd * g[3];
+            b.x = b.x * rstd * g[4]; b.y = b.y * rstd * g[5]; b.z = b.z * rstd * g[6]; b.w = b.w * rstd * g[7];
+        }
+        xs[v] = a;
+        xs[nvec + v] = b;
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same against M staged vectors at once (vector m at xs + 2 nvec m): every weight vector is loaded and
+// unpacked once and used for all M dot products.  The verify step of speculative decoding streams the
+// weights once for M positions this way.
+// ------------------------------------------------------------------------------------------------
+template <int DT, int NR, int U, int M>
+__device__ __forceinline__ void chunk_fma_m(const Chunk<NR, U> &c, const float4 *xs, int v0, int nvec,
+                                            float (&acc)[M][NR]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int v = v0 + u * WAVE;
+        if (v < nvec) {
+            float f[NR][8];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) unpack8<DT>(c.w[u][r], f[r]);
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const float4 a = xs[2 * nvec * m + v], b = xs[2 * nvec * m + nvec + v];
+#pragma unroll
+                for (int r = 0; r < NR; ++r) {
+                    float s = acc[m][r];
+                    s = fmaf(f[r][0], a.x, s); s = fmaf(f[r][1], a.y, s); s = fmaf(f[r][2], a.z, s); s = fmaf(f[r][3], a.w, s);
+                    s = fmaf(f[r][4], b.x, s); s = fmaf(f[r][5], b.y, s); s = fmaf(f[r][6], b.z, s); s = fmaf(f[r][7], b.w, s);
+                    acc[m][r] = s;
+                }
+            }
+        }
+    }
+}
+
+// Partial dot products over vectors [vbeg, vend) of the rows (a slice of K), accumulated into acc; xs holds that
+// slice of the M staged vectors (vector m at xs + 2 (vend - vbeg) m).  `pre` may hold the chunk at vbeg + lane.
+template <int DT, int NR, int U, int M>
+__device__ __forceinline__ void wave_dots_m(const uint16_t *const (&rows)[NR], const float4 *xs, int vbeg, int vend,
+                                            int lane, float (&acc)[M][NR], Chunk<NR, U> &pre, bool have_pre) {
+    const int nslice = vend - vbeg;
+    const uint16_t *shifted[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) shifted[r] = rows[r] + (size_t)vbeg * 8;
+    for (int v0 = lane; v0 < nslice; v0 += WAVE * U) {
+        if (!have_pre) chunk_load<NR, U>(pre, shifted, v0, nslice);
+        have_pre = false;
+        chunk_fma_m<DT, NR, U, M>(pre, xs, v0, nslice, acc);
+    }
+}
+
 }  // namespace efm

@@ -37,10 +37,12 @@ void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, co
                 const float *rope_sin, const int *d_pos, float *q, uint16_t *kcache_l, uint16_t *vcache_l,
                 hipStream_t st);
 // o <- softmax(q K^T / sqrt(d)) V over cache rows 0..pos, split over the context and merged
-// warm_w: W_o of this layer (workgroups without a context slice pull it into L2 for launch_gemv_resid) or null
+// warm_w: W_o of this layer (workgroups without a context slice pull it into L2 for launch_gemv_resid) or null.
+// n_queries > 1: query m (q, o at + m n_q d; part and counters at + m times their single-query size) is at
+// position pos + m and sees keys 0 .. pos + m.
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kcache_l,
                         const uint16_t *vcache_l, const int *d_pos, float *part, uint32_t *counters, float *o,
-                        const uint16_t *warm_w, hipStream_t st);
+                        const uint16_t *warm_w, int n_queries, hipStream_t st);
 // x <- x + W vec   (O projection: vec = o, K = n_q d;  down projection: vec = h, K = I)
 void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, const float *vec, float *x,
                        hipStream_t st);
@@ -58,6 +60,24 @@ void launch_set_int(int *p, int v, hipStream_t st);
 void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st);
 void launch_copy16(const void *src, void *dst, size_t bytes, hipStream_t st);
 int lmhead_blocks(const Dims &D, const Geo &G);
+
+// ------------------------------------------------------------------ decode kernels for M <= MULTI_MAX positions
+// (decode_multi.hip: the verification pass of speculative decoding, Section 3.11, as GEMVs that stream the
+// weights once for the whole block).  Activations are [M][.] fp32; position m of the block is context position
+// pos + m (pos read from device memory).
+constexpr int MULTI_MAX = 4;
+hipError_t multi_prepare();                                 // raise the LDS ceiling of the kernels once
+bool multi_supported(const Dims &D, const Geo &G, int M);  // the shape fits their LDS staging and grids
+void launch_embed_m(const Dims &D, int M, const uint16_t *embed, const int *d_tok, float *x, hipStream_t st);
+void launch_qkv_m(const Dims &D, const Geo &G, int M, const LayerW &W, const float *x, const float *rope_cos,
+                  const float *rope_sin, const int *d_pos, float *q, uint16_t *kcache_l, uint16_t *vcache_l,
+                  hipStream_t st);
+void launch_gemv_resid_m(const Dims &D, const Geo &G, int M, const uint16_t *W, int K, const float *vec, float *x,
+                         hipStream_t st);
+void launch_gateup_m(const Dims &D, const Geo &G, int M, const LayerW &W, const float *x, float *h, hipStream_t st);
+// logits [M][n] (n = vocab, or n_subset in subset order); hidden [M][H]
+void launch_lmhead_m(const Dims &D, const Geo &G, int M, const uint16_t *lm, const uint16_t *final_norm, const float *x,
+                     float *logits, float *hidden, const int *subset, int n_subset, hipStream_t st);
 
 // ------------------------------------------------------------------ fused decode step (one launch per token)
 enum { MEPI_STORE = 0, MEPI_RESID = 1, MEPI_SWIGLU = 2, MEPI_LOGITS = 3, MEPI_ATTN = 4 };
@@ -128,9 +148,9 @@ void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const
 
 // next_rows[t] <- argmax_i logits[t][i] over the vocabulary or the candidate ids (lowest id on ties);
 // d_next, d_token <- next_rows[T-1]
-// (part_val, part_idx: scratch for 32 T partials)
-void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, float *part_val,
-                        int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st);
+// (part_val, part_idx: scratch for 32 T partials).  compact: logits is [T][n_subset], column i belonging to subset[i].
+void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, bool compact,
+                        float *part_val, int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st);
 // out[t][i] <- logits[t][subset[i]]
 void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,
                           hipStream_t st);

@@ -32,6 +32,7 @@ struct Layout {
     size_t X, Ahi, Alo, QKV, Qs, Ohi, Olo, Hhi, Hlo, Kf, Vt, tok, gemm_ws;
     size_t subset;  // [vocab] int32: candidate token ids of a pruned vocabulary
     size_t flash_part;  // key-split partial records of the prefill attention
+    size_t mx, mq, mo, mh, mhidden;  // activations of the multi-position decode kernels: [MULTI_MAX][.] fp32
     size_t p_lm, vlogits, vgather, vnext;  // verify step: f16 copy of lm_head, [32][vocab] logits (raw, gathered), tokens
     size_t total;
 };
@@ -104,8 +105,8 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.q = take(qd * 4);
     L.o = take(qd * 4);
     L.h = take(I * 4);
-    L.part = take((size_t)c->n_q_heads * ATTN_SPLITS * (d + 4) * 4);
-    L.counters = take(c->n_kv_heads * 4);
+    L.part = take((size_t)MULTI_MAX * c->n_q_heads * ATTN_SPLITS * (d + 4) * 4);
+    L.counters = take((size_t)MULTI_MAX * c->n_kv_heads * 4);
     L.logits = take(V * 4);
     L.hidden = take(H * 4);
     L.part_val = take(MAX_PARTIALS * 4);
@@ -131,6 +132,11 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.gemm_ws = take(GEMM_WS_BYTES);
     L.subset = take(V * 4);
     L.flash_part = take(FLASH_PART_RECORDS * 128 * (d + 2) * 4);
+    L.mx = take(MULTI_MAX * H * 4);
+    L.mq = take(MULTI_MAX * qd * 4);
+    L.mo = take(MULTI_MAX * qd * 4);
+    L.mh = take(MULTI_MAX * I * 4);
+    L.mhidden = take(MULTI_MAX * H * 4);
     L.p_lm = take(V * H * 2);
     L.vlogits = take((size_t)VERIFY_MAX * V * 4);
     L.vgather = take((size_t)VERIFY_MAX * V * 4);
@@ -163,6 +169,8 @@ struct edgefm_model {
     int32_t *pin_next; // [1]
     int n_part;        // lm_head partial count
     uint32_t n_subset; // candidate tokens of a pruned vocabulary (0 = the whole vocabulary)
+    bool multi_ok;     // the multi-position decode kernels may be used for short verify blocks
+    bool verify_was_gemv;  // which buffers hold the last verify step's hidden states
     std::vector<LayerW> LW;
     struct PrefillW { const uint16_t *wqkv, *wo, *w_gate_up, *w_down; };
     std::vector<PrefillW> PW;
@@ -199,7 +207,7 @@ void enqueue_decode(edgefm_model *m, hipStream_t st) {
         launch_qkv(D, m->G, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
                    m->vc(l), st);
         launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                           m->at<uint32_t>(m->L.counters), o, W.wo, st);
+                           m->at<uint32_t>(m->L.counters), o, W.wo, 1, st);
         launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st);
         launch_gateup(D, m->G, W, x, h, st);
         launch_gemv_resid(D, m->G, W.w_down, D.I, h, x, st);
@@ -330,6 +338,12 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     }
     LOADCHK(kernels_prepare(D));
     {
+        // EDGEFM_VERIFY=gemm keeps every verify block on the m-row GEMM path
+        const char *vm = getenv("EDGEFM_VERIFY");
+        m->multi_ok = !(vm && vm[0] == 'g') && multi_prepare() == hipSuccess;
+        m->verify_was_gemv = false;
+    }
+    {
         // The fused single-launch step is correct but, as measured, slower than the graph of per-stage kernels
         // (its grid barriers queue behind the weight stream they try to overlap); EDGEFM_DECODE=fused selects it.
         const char *dm = getenv("EDGEFM_DECODE");
@@ -420,7 +434,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     }
     launch_fill_u16(m->at<uint16_t>(m->L.sync), 32, 0, m->stream);
     // attention arrival counters and the step parameters start at zero (fill kernel, not a memset node)
-    launch_fill_u16(m->at<uint16_t>(m->L.counters), (size_t)D.nkv * 2, 0, m->stream);
+    launch_fill_u16(m->at<uint16_t>(m->L.counters), (size_t)MULTI_MAX * D.nkv * 2, 0, m->stream);
     launch_fill_u16(m->at<uint16_t>(m->L.ints), 32, 0, m->stream);
     LOADCHK(hipStreamSynchronize(m->stream));
     LOADCHK(hipGetLastError());
@@ -539,22 +553,48 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
     if (logits_host && !m->pin_vlogits)
         HIPCHK(m, hipHostMalloc(reinterpret_cast<void **>(&m->pin_vlogits), (size_t)VERIFY_MAX * D.V * 4, hipHostMallocDefault));
     hipStream_t st = m->stream;
-    rc = enqueue_layers(m, tok_host, n_tokens, nullptr, 0, false);
-    if (rc != EDGEFM_OK) return rc;
-    // every new position needs its prediction: final norm and lm_head as a T-row GEMM against the f16 copy
-    uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo);
     float *vlogits = m->at<float>(m->L.vlogits);
     const int *subset = m->n_subset ? m->at<int>(m->L.subset) : nullptr;
-    launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);
-    launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
-                m->at<float>(m->L.gemm_ws), st);
-    launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, m->at<float>(m->L.part_val), m->at<int>(m->L.part_idx),
-                       m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
-    launch_set_int(m->d_pos(), ctx, st);
     const float *src = vlogits;
-    if (logits_host && subset) {
-        launch_gather_logits(vlogits, T, D.V, subset, (int)m->n_subset, m->at<float>(m->L.vgather), st);
-        src = m->at<float>(m->L.vgather);
+    m->verify_was_gemv = m->multi_ok && multi_supported(D, m->G, T);
+    if (m->verify_was_gemv) {
+        // Short blocks: the decode kernels with M activation vectors -- one pass over the weights, GEMV streaming
+        // rate, attention per position over the cache (which the QKV epilogue has just extended by the block).
+        memcpy(m->pin_tok, tok_host, (size_t)T * 4);
+        int *tok = m->at<int>(m->L.tok);
+        HIPCHK(m, hipMemcpyAsync(tok, m->pin_tok, (size_t)T * 4, hipMemcpyHostToDevice, st));
+        float *x = m->at<float>(m->L.mx), *q = m->at<float>(m->L.mq), *o = m->at<float>(m->L.mo), *h = m->at<float>(m->L.mh);
+        launch_embed_m(D, T, m->at<uint16_t>(m->L.embed), tok, x, st);
+        for (int l = 0; l < D.L; ++l) {
+            const LayerW &W = m->LW[l];
+            launch_qkv_m(D, m->G, T, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
+                         m->vc(l), st);
+            launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
+                               m->at<uint32_t>(m->L.counters), o, nullptr, T, st);
+            launch_gemv_resid_m(D, m->G, T, W.wo, D.qd(), o, x, st);
+            launch_gateup_m(D, m->G, T, W, x, h, st);
+            launch_gemv_resid_m(D, m->G, T, W.w_down, D.I, h, x, st);
+        }
+        launch_lmhead_m(D, m->G, T, m->lm(), m->at<uint16_t>(m->L.final_norm), x, vlogits, m->at<float>(m->L.mhidden),
+                        subset, (int)m->n_subset, st);  // logits already in candidate order
+        launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, true, m->at<float>(m->L.part_val),
+                           m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
+        launch_set_int(m->d_pos(), ctx, st);
+    } else {
+        rc = enqueue_layers(m, tok_host, n_tokens, nullptr, 0, false);
+        if (rc != EDGEFM_OK) return rc;
+        // every new position needs its prediction: final norm and lm_head as a T-row GEMM against the f16 copy
+        uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo);
+        launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);
+        launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
+                    m->at<float>(m->L.gemm_ws), st);
+        launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, false, m->at<float>(m->L.part_val),
+                           m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
+        launch_set_int(m->d_pos(), ctx, st);
+        if (logits_host && subset) {
+            launch_gather_logits(vlogits, T, D.V, subset, (int)m->n_subset, m->at<float>(m->L.vgather), st);
+            src = m->at<float>(m->L.vgather);
+        }
     }
     HIPCHK(m, hipGetLastError());
     m->kv_len = (uint32_t)ctx;
@@ -699,8 +739,13 @@ int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n) {
 int edgefm_debug_verify_hidden(edgefm_model *m, uint32_t row, float *hidden_host) {
     if (!m || !hidden_host || row >= VERIFY_MAX) return EDGEFM_ERR_INVALID_ARG;
     const size_t H = (size_t)m->D.H;
-    std::vector<uint16_t> hi(H), lo(H);
     HIPCHK(m, hipStreamSynchronize(m->stream));
+    if (m->verify_was_gemv) {
+        if (row >= (uint32_t)MULTI_MAX) return EDGEFM_ERR_INVALID_ARG;
+        HIPCHK(m, hipMemcpy(hidden_host, m->at<float>(m->L.mhidden) + row * H, H * 4, hipMemcpyDeviceToHost));
+        return EDGEFM_OK;
+    }
+    std::vector<uint16_t> hi(H), lo(H);
     HIPCHK(m, hipMemcpy(hi.data(), m->at<uint16_t>(m->L.Ahi) + row * H, H * 2, hipMemcpyDeviceToHost));
     HIPCHK(m, hipMemcpy(lo.data(), m->at<uint16_t>(m->L.Alo) + row * H, H * 2, hipMemcpyDeviceToHost));
     auto f16 = [](uint16_t b) -> float {  // IEEE binary16 -> float
@@ -750,7 +795,7 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) 
                 break;
             case EDGEFM_OP_ATTN:
                 launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                                   m->at<uint32_t>(m->L.counters), o, W.wo, st);
+                                   m->at<uint32_t>(m->L.counters), o, W.wo, 1, st);
                 break;
             case EDGEFM_OP_OPROJ: launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st); break;
             case EDGEFM_OP_GATEUP: launch_gateup(D, m->G, W, x, h, st); break;

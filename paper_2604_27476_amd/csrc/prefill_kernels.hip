@@ -961,18 +961,18 @@ k_flash_merge(const float *__restrict__ part, int n_splits, int T, int p0, uint1
 // ------------------------------------------------------------------------------------------------
 constexpr int ARGMAX_CHUNKS = 32;
 __global__ void __launch_bounds__(256)
-k_argmax_rows(const float *__restrict__ logits, int V, const int *__restrict__ subset, int n_subset,
+k_argmax_rows(const float *__restrict__ logits, int V, const int *__restrict__ subset, int n_subset, int compact,
               float *__restrict__ part_val, int *__restrict__ part_idx) {
     __shared__ float bv[4];
     __shared__ int bi[4];
-    const float *row = logits + (size_t)blockIdx.y * V;
+    const float *row = logits + (size_t)blockIdx.y * (compact ? n_subset : V);
     const int n = subset ? n_subset : V;
     const int per = (n + ARGMAX_CHUNKS - 1) / ARGMAX_CHUNKS, beg = blockIdx.x * per, end = min(n, beg + per);
     float best = -INFINITY;
     int best_i = 0x7fffffff;
     for (int i = beg + threadIdx.x; i < end; i += 256) {  // ids are visited in increasing order per thread
         const int id = subset ? subset[i] : i;
-        const float v = row[id];
+        const float v = row[compact ? i : id];
         if (v > best) { best = v; best_i = id; }
     }
 #pragma unroll
@@ -1227,9 +1227,10 @@ void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const
     }
 }
 
-void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, float *part_val,
-                        int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st) {
-    hipLaunchKernelGGL(k_argmax_rows, dim3(ARGMAX_CHUNKS, T), dim3(256), 0, st, logits, V, subset, n_subset, part_val, part_idx);
+void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, bool compact,
+                        float *part_val, int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st) {
+    hipLaunchKernelGGL(k_argmax_rows, dim3(ARGMAX_CHUNKS, T), dim3(256), 0, st, logits, V, subset, n_subset,
+                       (subset && compact) ? 1 : 0, part_val, part_idx);
     hipLaunchKernelGGL(k_argmax_rows_finish, dim3((T + 63) / 64), dim3(64), 0, st, part_val, part_idx, T, subset, next_rows,
                        d_next, d_token);
 }

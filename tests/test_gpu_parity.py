@@ -425,12 +425,12 @@ def test_verify_step_equals_block_forward_and_decode_steps():
     rng = np.random.default_rng(3)
     P.prefill(prompt)
     pos = 37
-    for m in (1, 2, 5, 8, 32):
+    for m in (1, 2, 3, 4, 5, 8, 32):                  # up to 4: the decode kernels on M vectors; beyond: the m-row GEMMs
         block = rng.integers(0, shape.vocab, size=m).astype(np.int32)
         _check_verify(P, block, f"verify m={m}")
         pos += m
         assert g.kv_len == pos == o.kv_len
-    P.check_kv([0, 1], [36, 37, 40, pos - 1])
+    P.check_kv([0, 1], [36, 37, 38, 39, 40, 43, 46, pos - 1])
     # a block from an empty context (positions 0..m-1)
     g.kv_reset(0); o.kv_reset(0)
     _check_verify(P, prompt[:9], "verify from empty")
@@ -479,7 +479,9 @@ def test_verify_step_equals_block_forward_and_decode_steps():
     subset = np.sort(rng.choice(shape.vocab, size=211, replace=False)).astype(np.int32)
     g.set_vocab_subset(subset)
     g.kv_reset(0); o.kv_reset(0)
-    _check_verify(P, prompt[:7], "verify with subset", subset=subset)
+    _check_verify(P, prompt[:7], "verify with subset", subset=subset)          # m-row GEMM path
+    _check_verify(P, prompt[7:10], "verify with subset, short block", subset=subset)   # multi-position GEMV path
+    assert g.kv_len == 10
     g.set_vocab_subset(None)
     E = binding.EdgefmError
     for bad in (np.zeros(0, np.int32), np.zeros(33, np.int32)):
@@ -501,9 +503,9 @@ def test_verify_step_7b_width_context_1000():
         P.gm.kv_write(l, k, v)
     P.gm.set_kv_len(ctx)
     rng = np.random.default_rng(4)
-    for m in (4, 8):
+    for m in (4, 8, 3, 2):
         _check_verify(P, rng.integers(0, shape.vocab, size=m).astype(np.int32), f"7b-width verify m={m}")
-    assert P.gm.kv_len == ctx + 12
+    assert P.gm.kv_len == ctx + 17
     print(f"verify 7b-width worst {P.worst}")
 
 
