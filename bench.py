@@ -116,6 +116,22 @@ def sweep(args) -> int:
             print(json.dumps({"shape": name, "kind": "verify_step", "context": C, "block_tokens": mm,
                               "ms_per_step": round(float(np.mean(ts[2:])), 4),
                               "ms_per_token_if_all_accepted": round(float(np.mean(ts[2:])) / mm, 4)}), flush=True)
+        if args.sweep_oracle:  # the oracle beside it: a reported baseline on this host's cores, not a target
+            import oracle
+            om = oracle.OracleModel(shape, w)
+            Tp = {"qwen2.5-0.5b-shaped": 128, "qwen2.5-1.5b-shaped": 512}.get(name, 128)
+            t0 = time.perf_counter()
+            r = om.prefill(synth.make_prompt(shape, Tp), want_hidden=False)
+            t_pf = time.perf_counter() - t0
+            tok = int(r["next"][0])
+            t0 = time.perf_counter()
+            for _ in range(3):
+                tok = int(om.decode_step(tok, want_hidden=False)["next"][0])
+            t_dec = (time.perf_counter() - t0) / 3
+            print(json.dumps({"shape": name, "kind": "cpu_oracle", "cores": oracle.num_threads(), "prefill_tokens": Tp,
+                              "prefill_ms": round(t_pf * 1e3, 1), "decode_ms_per_token": round(t_dec * 1e3, 2),
+                              "decode_context": Tp}), flush=True)
+            del om
         if name == "qwen2.5-7b-shaped":  # image rows + text ids as one prefill, short generation, latency percentiles
             emb = torch.from_numpy(np.ascontiguousarray(synth.make_visual_embeds(shape, 1024)).view(np.int16)).to(gm.device)
             torch.cuda.synchronize()  # the rows are resident before any timed request
@@ -140,6 +156,8 @@ def main() -> int:
     ap.add_argument("--decode", type=int, default=64)
     ap.add_argument("--shape", default="qwen2.5-7b-shaped")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-oracle", action="store_true",
+                    help="with --sweep: also time the CPU oracle on every shape (decode steps and one prefill; minutes)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline line: TTFT over prompt lengths and decode latency over context "
                          "lengths for every configured shape, one JSON object per line")
