@@ -10,8 +10,8 @@
 //   GEMMs:      a = a_hi + a_lo in f16 (22 significant bits) against an f16 copy of the weights scaled
 //               by 2^8 (the prefill artifact theta_p of Section 3.5; exact for every bf16/f16 weight of
 //               magnitude >= 2^-25), two MFMAs per product;
-//   attention:  q and p as three bf16 terms (24 bits) against the bf16 cache, or two f16 terms against an
-//               f16 cache: the cache operands are used exactly as stored.
+//   attention:  q and p as two f16 terms each against f16 copies of the cached K and V rows (k_prep_kv; every
+//               bf16 value of magnitude 2^-14 .. 65504 is an f16 value, so the copies are exact).
 #include <stdlib.h>
 
 #include <algorithm>
