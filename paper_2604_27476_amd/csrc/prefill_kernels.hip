@@ -1207,10 +1207,11 @@ void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const
                        int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, float *part, hipStream_t st) {
     const int nqb = (T + 127) / 128, units = nqb * D.nq;
     // Few (query block, head) units leave CUs idle and make the last block's key loop the whole duration: cut
-    // the key range so that about two workgroups per CU exist (at most 8 splits, at most the tile count, and
-    // within the records the scratch holds).
+    // the key range so that about one workgroup per CU exists (at most 8 splits, at most the tile count, and
+    // within the records the scratch holds).  With a unit per CU already (T = 1024 on 28 heads) the merge pass
+    // costs what the shorter key loops save, so such launches stay whole.
     const int max_tiles = (p0 + T - 1) / 64 + 1;
-    int n_splits = part ? std::min(std::min(8, max_tiles), std::max(1, 512 / units)) : 1;
+    int n_splits = part ? std::min(std::min(8, max_tiles), std::max(1, 320 / units)) : 1;
     while (n_splits > 1 && (size_t)units * n_splits > FLASH_PART_RECORDS) --n_splits;
     const dim3 grid(units * n_splits), block(256);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D.d);
