@@ -431,9 +431,31 @@ def test_verify_step_equals_block_forward_and_decode_steps():
         pos += m
         assert g.kv_len == pos == o.kv_len
     P.check_kv([0, 1], [36, 37, 38, 39, 40, 43, 46, pos - 1])
-    # a block from an empty context (positions 0..m-1)
+    # blocks from an empty context (positions 0..m-1), on both routes
     g.kv_reset(0); o.kv_reset(0)
     _check_verify(P, prompt[:9], "verify from empty")
+    g.kv_reset(0); o.kv_reset(0)
+    _check_verify(P, prompt[:3], "short verify from empty")
+    # a short block whose positions straddle an attention-slice boundary (keys 0..61 | 62..65)
+    g.kv_reset(0); o.kv_reset(0)
+    P.prefill(synth.make_prompt(shape, 62, seed=9), where="prefill 62")
+    _check_verify(P, prompt[3:7], "verify across the 64-key slice boundary")
+    P.check_kv([0, 1], [61, 62, 63, 64, 65])
+    # error paths leave the context as it was
+    E = binding.EdgefmError
+    with pytest.raises(E) as e:
+        g.verify_step(np.array([1, shape.vocab], np.int32))
+    assert e.value.status == binding.EDGEFM_ERR_BAD_TOKEN
+    assert g.kv_len == 66
+    g.kv_reset(0)
+    g.prefill(synth.make_prompt(shape, 150, seed=10), want_logits=False)
+    for m in (11, 3 + 8):                               # 150 + 11 > 160 on either route
+        with pytest.raises(E) as e:
+            g.verify_step(np.zeros(m, np.int32) + 5)
+        assert e.value.status == binding.EDGEFM_ERR_CONTEXT_OVERFLOW
+    assert g.kv_len == 150
+    g.verify_step(np.zeros(4, np.int32) + 5)            # 154: still fits
+    assert g.kv_len == 154
     # same predictions as explicit decode steps (different kernels), then chained decode from the last one
     g.kv_reset(0)
     g.prefill(prompt, want_logits=False)
