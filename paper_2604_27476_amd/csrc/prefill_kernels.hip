@@ -295,7 +295,9 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 // Pipelined GEMM (same contract as k_gemm; K must be a multiple of 32): 256 x 256 x 32 workgroup tile,
 // eight waves in 4 x 2, each wave 64 x 128 (WM = 4: TM = 2, TN = 4, 0.5 LDS fragment reads per MFMA); or, for
 // prompts that would leave most of a 256-row tile empty, 128 x 256 x 32 with the waves in 2 x 4, each 64 x 64
-// (WM = 2).  The three
+// (WM = 2); or, for blocks of at most 64 rows (verify steps, very short prompts), 64 x 256 x 32 with the waves
+// in 1 x 8, each 64 x 32 (WM = 1: little MFMA work per k-tile, the loop runs at the pace of its barriers and
+// streams the weights).  The three
 // operand tiles go from global memory straight into LDS (global_load_lds, no staging registers, no
 // ds_write) through a ring of three stages, two to three k-tiles ahead of the MFMAs, with one barrier per
 // k-tile.  LDS rows are 64 bytes (4 chunks of 16 B); chunk c of row r sits in slot c ^ ((r >> 1) & 3),
@@ -315,6 +317,7 @@ static_assert((size_t)256 * P_BN * 4 * 256 <= GEMM_WS_BYTES, "a split round (sli
 // ws[(slice * n_tiles + local tile)][bm][256] and k_splitk_finish adds the slices up in a fixed order.
 struct PipeRange {
     int n_mt, n_nt, tile_begin, n_tiles, k_splits, bm;
+    int wn_out;  // SwiGLU outputs per wave tile: the tile's columns are wn_out gate rows, wn_out up rows, ...
     float *ws;
 };
 __device__ __forceinline__ void pipe_tile(const PipeRange &R, int tl, int &mt, int &nb) {
@@ -382,15 +385,18 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     // DMA plan: one instruction moves 16 rows x 64 B.  Wave w issues, per stage, instructions A_I w .. A_I w + A_I - 1
     // of the two A tiles and 2w, 2w + 1 of the B tile.  Lane l of an instruction covers row R0 + l/4, slot l%4,
     // i.e. logical chunk (l%4) ^ ((row >> 1) & 3).
-    constexpr int A_I = BM / 128, B_I = P_BN / 128;
+    // With WM = 1 the two A tiles are 4 instructions each: waves 0-3 take one of A_hi, waves 4-7 one of A_lo.
+    constexpr int A_I = BM >= 128 ? BM / 128 : 1, B_I = P_BN / 128;
+    constexpr bool A_SPLIT = BM < 128;  // a wave loads from one of the two A tiles only
     uint32_t ga[A_I], gb[B_I];  // byte offsets of this lane's chunk at k0 = 0 (A_hi and A_lo share ga)
     int la[A_I], lb[B_I];       // LDS byte offset of the instruction's first row
 #pragma unroll
     for (int i = 0; i < A_I; ++i) {
-        const int r = 16 * (A_I * wave + i) + (lane >> 2);
+        const int inst = A_SPLIT ? (wave & 3) : A_I * wave + i;
+        const int r = 16 * inst + (lane >> 2);
         const int c = (lane & 3) ^ ((r >> 1) & 3);
         ga[i] = ((uint32_t)min(m0 + r, T - 1) * (uint32_t)K + c * 8) * 2u;
-        la[i] = 16 * (A_I * wave + i) * PK * 2;
+        la[i] = 16 * inst * PK * 2;
     }
 #pragma unroll
     for (int i = 0; i < B_I; ++i) {
@@ -402,10 +408,15 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     auto issue = [&](int kt) {
         const uint32_t st = lds_addr(ring) + (kt % P_STAGES) * (STAGE_ELEMS * 2);
         const int k0 = kt * PK;
+        if constexpr (A_SPLIT) {
+            if (wave < 4) lds_dma16(Ahi + k0, ga[0], st + la[0]);
+            else lds_dma16(Alo + k0, ga[0], st + BM * PK * 2 + la[0]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < A_I; ++i) {
-            lds_dma16(Ahi + k0, ga[i], st + la[i]);
-            lds_dma16(Alo + k0, ga[i], st + BM * PK * 2 + la[i]);
+            for (int i = 0; i < A_I; ++i) {
+                lds_dma16(Ahi + k0, ga[i], st + la[i]);
+                lds_dma16(Alo + k0, ga[i], st + BM * PK * 2 + la[i]);
+            }
         }
 #pragma unroll
         for (int i = 0; i < B_I; ++i) lds_dma16(W + k0, gb[i], st + 2 * BM * PK * 2 + lb[i]);
@@ -465,12 +476,13 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     Frag f0, f1;
     issue(0);
     if (nk > 1) issue(1);
-    constexpr int NI = 2 * A_I + B_I;  // this wave's LDS-DMA instructions per k-tile
-    static_assert(NI == 6 || NI == 4, "the vmcnt immediates below are written for these two shapes");
-#define WAIT_ALL_BUT_ONE_TILE(extra)                                                   \
-    do {                                                                               \
-        if constexpr (NI == 6) asm volatile("s_waitcnt vmcnt(6)" extra ::: "memory");  \
-        else asm volatile("s_waitcnt vmcnt(4)" extra ::: "memory");                    \
+    constexpr int NI = (A_SPLIT ? 1 : 2 * A_I) + B_I;  // this wave's LDS-DMA instructions per k-tile
+    static_assert(NI == 6 || NI == 4 || NI == 3, "the vmcnt immediates below are written for these shapes");
+#define WAIT_ALL_BUT_ONE_TILE(extra)                                                        \
+    do {                                                                                    \
+        if constexpr (NI == 6) asm volatile("s_waitcnt vmcnt(6)" extra ::: "memory");       \
+        else if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(4)" extra ::: "memory");  \
+        else asm volatile("s_waitcnt vmcnt(3)" extra ::: "memory");                         \
     } while (0)
     if (nk > 1) WAIT_ALL_BUT_ONE_TILE("");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -536,7 +548,18 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         for (int i = 0; i < 16; ++i) {
             const int m = m0 + wm * 64 + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
             if (m >= T) continue;
-            if constexpr (EPI == EPI_SWIGLU) {
+            if constexpr (EPI == EPI_SWIGLU && TN == 1) {
+                // the wave's 32 columns are 16 gate rows, then the 16 up rows of the same neurons: lanes fr and
+                // fr + 16 (same row of the tile) hold the two halves of one output
+                const float g = acc[a][0][i] * UNSCALE, u = __shfl_xor(acc[a][0][i], 16, WAVE) * UNSCALE;
+                const int j = nb * (P_BN / 2) + wn * (WN / 2) + (fr & 15);
+                if ((fr & 16) == 0 && j < N) {
+                    uint16_t h, l;
+                    split_f16(g / (1.0f + expf(-g)) * u, h, l);
+                    ohi[(size_t)m * N + j] = h;
+                    olo[(size_t)m * N + j] = l;
+                }
+            } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
                 for (int b = 0; b < TN / 2; ++b) {
                     const int j = nb * (P_BN / 2) + wn * (WN / 2) + b * 32 + fr;
@@ -579,7 +602,7 @@ k_splitk_finish(PipeRange R, int T, int N, const uint16_t *__restrict__ bias, fl
     pipe_tile(R, tl, mt, nb);
     const size_t slice = (size_t)R.n_tiles * (R.bm * P_BN);
     const float *wt = R.ws + (size_t)tl * (R.bm * P_BN);
-    const int wn_out = 16 * (R.bm / 64);  // outputs per wave tile row: 32 TN / 2 with TN = bm / 64
+    const int wn_out = R.wn_out;
     const int o = (threadIdx.x % TPR) * 4;
 #pragma unroll
     for (int pass = 0; pass < FIN_ROWS / RPI; ++pass) {
@@ -1075,7 +1098,8 @@ static bool gemm_pipe_enabled() {
                                    hipFuncAttributeMaxDynamicSharedMemorySize,                                 \
                                    P_STAGES * pipe_stage_elems(WM) * 2) == hipSuccess;
 #define PIPE_ATTR_EPI(BDT, WM) PIPE_ATTR(BDT, EPI_SWIGLU, WM) PIPE_ATTR(BDT, EPI_RESID, WM) PIPE_ATTR(BDT, EPI_BIAS_F32, WM)
-        PIPE_ATTR_EPI(DT_BF16, 4) PIPE_ATTR_EPI(DT_BF16, 2) PIPE_ATTR_EPI(DT_F16, 4) PIPE_ATTR_EPI(DT_F16, 2)
+        PIPE_ATTR_EPI(DT_BF16, 4) PIPE_ATTR_EPI(DT_BF16, 2) PIPE_ATTR_EPI(DT_BF16, 1)
+        PIPE_ATTR_EPI(DT_F16, 4) PIPE_ATTR_EPI(DT_F16, 2) PIPE_ATTR_EPI(DT_F16, 1)
 #undef PIPE_ATTR_EPI
 #undef PIPE_ATTR
         state = ok ? 1 : 0;
@@ -1128,25 +1152,26 @@ static bool pipe_plan(int epi, const uint16_t *Ahi, const uint16_t *Alo, const u
     const int n_cu = std::min(device_cu_count(), 256), tiles = n_mt * n_nt, nk = K / PK;
     const int rem = tiles % n_cu, full = tiles - rem;
     int splits = 1;
-    if (rem > 0 && ws) splits = std::min(std::min(n_cu / rem, PIPE_MAX_SPLITS), nk / PIPE_MIN_SLICE_TILES);
+    if (rem > 0 && ws) splits = std::min(std::min(n_cu / rem, WM == 1 ? 2 * PIPE_MAX_SPLITS : PIPE_MAX_SPLITS), nk / PIPE_MIN_SLICE_TILES);
     if (splits < 2) {
         if (tiles * 2 < n_cu) return false;  // fewer than half of the CUs would work: leave it to the tile kernels
-        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, tiles, 1, BM, nullptr}, st);
+        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, tiles, 1, BM, 16 * WM, nullptr}, st);
         return true;
     }
     if (full > 0)
-        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, full, 1, BM, nullptr}, st);
-    pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, full, rem, splits, BM, ws}, st);
+        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, full, 1, BM, 16 * WM, nullptr}, st);
+    pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, full, rem, splits, BM, 16 * WM, ws}, st);
     return true;
 }
 
 template <int BDT>
 static void gemm_rows(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                       const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, bool pipe_ok,
-                      bool rows128, hipStream_t st) {
+                      int wm, hipStream_t st) {
     if (pipe_ok) {
-        const bool done = rows128 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st)
-                                  : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st);
+        const bool done = wm == 1   ? pipe_plan<BDT, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st)
+                          : wm == 2 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st)
+                                    : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st);
         if (done) return;
     }
     // largest tile that still gives every one of the 256 CUs two workgroups
@@ -1171,7 +1196,8 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
     // ... or, for prompts below 1024, would not even give every CU one tile.
     const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
     const bool rows128 = T < 1024 && ((T - 1) % 256 < 128 || ((T + 255) / 256) * n_nt < std::min(device_cu_count(), 256));
-    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, rows128, st);
+    // blocks of at most 64 rows: the 64-row tiles, whose k-loop streams the weights
+    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, T <= 64 ? 1 : (rows128 ? 2 : 4), st);
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
