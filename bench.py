@@ -3,7 +3,7 @@
 
 A "step" is one request of the Qwen2.5-7B-shaped workload (random bf16 weights, synthetic prompt):
 reset the KV slot, prefill PROMPT tokens, then DECODE greedy decode steps chained on the device.
-The headline value is the decode latency in ms/token (BASELINE metric); TTFT, the achieved HBM
+The headline value is the decode latency in ms/token; TTFT, the achieved HBM
 bandwidth of the decode step and the prefill TFLOP/s ride along in the same JSON line, together with
   * "roofline":     the dominant decode kernel (gate/up GEMV) timed alone with HIP events,
   * "cpu_baseline": the CPU oracle timed on this host on a bounded sample of the same workload.
