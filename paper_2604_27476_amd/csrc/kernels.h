@@ -147,10 +147,11 @@ void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const
                        int ctx_pad, int T, int p0, uint16_t *Ohi, uint16_t *Olo, float *part, hipStream_t st);
 
 // next_rows[t] <- argmax_i logits[t][i] over the vocabulary or the candidate ids (lowest id on ties);
-// d_next, d_token <- next_rows[T-1]
+// d_next, d_token <- next_rows[T-1]; d_pos += T
 // (part_val, part_idx: scratch for 32 T partials).  compact: logits is [T][n_subset], column i belonging to subset[i].
 void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, bool compact,
-                        float *part_val, int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st);
+                        float *part_val, int *part_idx, int *next_rows, int *d_next, int *d_token, int *d_pos,
+                        hipStream_t st);
 // out[t][i] <- logits[t][subset[i]]
 void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,
                           hipStream_t st);

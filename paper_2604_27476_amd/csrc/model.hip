@@ -157,6 +157,8 @@ struct edgefm_model {
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
     bool graph_ready, use_graph;
+    hipGraph_t vgraph[MULTI_MAX + 1];          // verify steps of 1..MULTI_MAX positions as captured graphs
+    hipGraphExec_t vgraph_exec[MULTI_MAX + 1];
     bool use_mega;         // decode step = one fused persistent kernel (shape-specialised), else the graph
     MegaArgs mega;
     uint32_t kv_len;       // host mirror of the device-side position counter
@@ -232,6 +234,58 @@ int build_graph(edgefm_model *m) {
     return EDGEFM_OK;
 }
 
+// A short verify block on the decode kernels with M activation vectors: one pass over the weights at the GEMV
+// streaming rate, attention per position over the cache (which the QKV epilogue has just extended by the block),
+// every position's prediction, and the position counter advanced by M.
+void enqueue_verify_gemv(edgefm_model *m, int T, hipStream_t st) {
+    const Dims &D = m->D;
+    const int *subset = m->n_subset ? m->at<int>(m->L.subset) : nullptr;
+    float *x = m->at<float>(m->L.mx), *q = m->at<float>(m->L.mq), *o = m->at<float>(m->L.mo), *h = m->at<float>(m->L.mh);
+    float *vlogits = m->at<float>(m->L.vlogits);
+    launch_embed_m(D, T, m->at<uint16_t>(m->L.embed), m->at<int>(m->L.tok), x, st);
+    for (int l = 0; l < D.L; ++l) {
+        const LayerW &W = m->LW[l];
+        launch_qkv_m(D, m->G, T, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
+                     m->vc(l), st);
+        launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
+                           m->at<uint32_t>(m->L.counters), o, nullptr, T, st);
+        launch_gemv_resid_m(D, m->G, T, W.wo, D.qd(), o, x, st);
+        launch_gateup_m(D, m->G, T, W, x, h, st);
+        launch_gemv_resid_m(D, m->G, T, W.w_down, D.I, h, x, st);
+    }
+    launch_lmhead_m(D, m->G, T, m->lm(), m->at<uint16_t>(m->L.final_norm), x, vlogits, m->at<float>(m->L.mhidden),
+                    subset, (int)m->n_subset, st);  // logits already in candidate order
+    launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, true, m->at<float>(m->L.part_val),
+                       m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), m->d_pos(), st);
+}
+
+int build_verify_graph(edgefm_model *m, int T) {
+    HIPCHK(m, hipStreamBeginCapture(m->cap_stream, hipStreamCaptureModeThreadLocal));
+    enqueue_verify_gemv(m, T, m->cap_stream);
+    hipError_t e = hipStreamEndCapture(m->cap_stream, &m->vgraph[T]);
+    if (e != hipSuccess) {
+        m->last_hip = (int)e;
+        return EDGEFM_ERR_HIP;
+    }
+    HIPCHK(m, hipGraphInstantiate(&m->vgraph_exec[T], m->vgraph[T], nullptr, nullptr, 0));
+    return EDGEFM_OK;
+}
+
+// The captured sequences hold the lm_head grid and row count of the candidate set they were recorded under.
+void drop_graphs(edgefm_model *m) {
+    if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
+    if (m->graph) (void)hipGraphDestroy(m->graph);
+    m->graph_exec = nullptr;
+    m->graph = nullptr;
+    m->graph_ready = false;
+    for (int i = 0; i <= MULTI_MAX; ++i) {
+        if (m->vgraph_exec[i]) (void)hipGraphExecDestroy(m->vgraph_exec[i]);
+        if (m->vgraph[i]) (void)hipGraphDestroy(m->vgraph[i]);
+        m->vgraph_exec[i] = nullptr;
+        m->vgraph[i] = nullptr;
+    }
+}
+
 size_t n_logits(const edgefm_model *m) { return m->n_subset ? m->n_subset : (size_t)m->D.V; }
 
 int fetch_outputs(edgefm_model *m, float *logits_host, int32_t *next_host) {
@@ -295,6 +349,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     m->graph = nullptr;
     m->graph_exec = nullptr;
     m->graph_ready = false;
+    for (int i = 0; i <= MULTI_MAX; ++i) { m->vgraph[i] = nullptr; m->vgraph_exec[i] = nullptr; }
     const char *ng = getenv("EDGEFM_NO_GRAPH");
     m->use_graph = !(ng && ng[0] == '1');
     m->kv_len = 0;
@@ -445,8 +500,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
 
 void edgefm_model_free(edgefm_model *m) {
     if (!m) return;
-    if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
-    if (m->graph) (void)hipGraphDestroy(m->graph);
+    drop_graphs(m);
     if (m->cap_stream) (void)hipStreamDestroy(m->cap_stream);
     if (m->pin_tok) (void)hipHostFree(m->pin_tok);
     if (m->pin_logits) (void)hipHostFree(m->pin_logits);
@@ -561,25 +615,16 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
         // Short blocks: the decode kernels with M activation vectors -- one pass over the weights, GEMV streaming
         // rate, attention per position over the cache (which the QKV epilogue has just extended by the block).
         memcpy(m->pin_tok, tok_host, (size_t)T * 4);
-        int *tok = m->at<int>(m->L.tok);
-        HIPCHK(m, hipMemcpyAsync(tok, m->pin_tok, (size_t)T * 4, hipMemcpyHostToDevice, st));
-        float *x = m->at<float>(m->L.mx), *q = m->at<float>(m->L.mq), *o = m->at<float>(m->L.mo), *h = m->at<float>(m->L.mh);
-        launch_embed_m(D, T, m->at<uint16_t>(m->L.embed), tok, x, st);
-        for (int l = 0; l < D.L; ++l) {
-            const LayerW &W = m->LW[l];
-            launch_qkv_m(D, m->G, T, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
-                         m->vc(l), st);
-            launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                               m->at<uint32_t>(m->L.counters), o, nullptr, T, st);
-            launch_gemv_resid_m(D, m->G, T, W.wo, D.qd(), o, x, st);
-            launch_gateup_m(D, m->G, T, W, x, h, st);
-            launch_gemv_resid_m(D, m->G, T, W.w_down, D.I, h, x, st);
+        HIPCHK(m, hipMemcpyAsync(m->at<int>(m->L.tok), m->pin_tok, (size_t)T * 4, hipMemcpyHostToDevice, st));
+        if (m->use_graph) {  // every step parameter lives in device memory, so one captured sequence per block length
+            if (!m->vgraph_exec[T]) {
+                rc = build_verify_graph(m, T);
+                if (rc != EDGEFM_OK) return rc;
+            }
+            HIPCHK(m, hipGraphLaunch(m->vgraph_exec[T], st));
+        } else {
+            enqueue_verify_gemv(m, T, st);
         }
-        launch_lmhead_m(D, m->G, T, m->lm(), m->at<uint16_t>(m->L.final_norm), x, vlogits, m->at<float>(m->L.mhidden),
-                        subset, (int)m->n_subset, st);  // logits already in candidate order
-        launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, true, m->at<float>(m->L.part_val),
-                           m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
-        launch_set_int(m->d_pos(), ctx, st);
     } else {
         rc = enqueue_layers(m, tok_host, n_tokens, nullptr, 0, false);
         if (rc != EDGEFM_OK) return rc;
@@ -589,8 +634,7 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
         launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
                     m->at<float>(m->L.gemm_ws), st);
         launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, false, m->at<float>(m->L.part_val),
-                           m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), st);
-        launch_set_int(m->d_pos(), ctx, st);
+                           m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), m->d_pos(), st);
         if (logits_host && subset) {
             launch_gather_logits(vlogits, T, D.V, subset, (int)m->n_subset, m->at<float>(m->L.vgather), st);
             src = m->at<float>(m->L.vgather);
@@ -651,13 +695,8 @@ int edgefm_set_vocab_subset(edgefm_model *m, const int32_t *ids_host, uint32_t n
         if (ids_host[i] < 0 || (uint32_t)ids_host[i] >= m->cfg.vocab) return EDGEFM_ERR_BAD_TOKEN;
         if (i > 0 && ids_host[i] <= ids_host[i - 1]) return EDGEFM_ERR_INVALID_ARG;  // strictly ascending
     }
-    // the captured step holds the lm_head grid and row count of the previous setting
     HIPCHK(m, hipStreamSynchronize(m->stream));
-    if (m->graph_exec) (void)hipGraphExecDestroy(m->graph_exec);
-    if (m->graph) (void)hipGraphDestroy(m->graph);
-    m->graph_exec = nullptr;
-    m->graph = nullptr;
-    m->graph_ready = false;
+    drop_graphs(m);
     if (n_ids > 0) {
         HIPCHK(m, hipMemcpyAsync(m->at<int>(m->L.subset), ids_host, (size_t)n_ids * 4, hipMemcpyHostToDevice, m->stream));
         HIPCHK(m, hipStreamSynchronize(m->stream));  // ids_host is the caller's again

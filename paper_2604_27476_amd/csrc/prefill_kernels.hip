@@ -1016,7 +1016,7 @@ k_argmax_rows(const float *__restrict__ logits, int V, const int *__restrict__ s
 __global__ void __launch_bounds__(64)
 k_argmax_rows_finish(const float *__restrict__ part_val, const int *__restrict__ part_idx, int T,
                      const int *__restrict__ subset, int *__restrict__ next_rows, int *__restrict__ d_next,
-                     int *__restrict__ d_token) {
+                     int *__restrict__ d_token, int *__restrict__ d_pos) {
     const int t = blockIdx.x * 64 + threadIdx.x;
     if (t >= T) return;
     float best = -INFINITY;
@@ -1028,7 +1028,11 @@ k_argmax_rows_finish(const float *__restrict__ part_val, const int *__restrict__
     }
     if (best_i == 0x7fffffff) best_i = subset ? subset[0] : 0;  // all NaN/-inf: still a valid id
     next_rows[t] = best_i;
-    if (t == T - 1) { d_next[0] = best_i; d_token[0] = best_i; }
+    if (t == T - 1) {  // the block's last prediction is the device-side current token; the context grew by T
+        d_next[0] = best_i;
+        d_token[0] = best_i;
+        d_pos[0] += T;
+    }
 }
 
 // out[t][i] = logits[t][subset[i]]: the candidates' logits in candidate order
@@ -1255,11 +1259,12 @@ void launch_flash_attn(const Dims &D, const uint16_t *Qs, size_t q_stride, const
 }
 
 void launch_argmax_rows(const float *logits, int T, int V, const int *subset, int n_subset, bool compact,
-                        float *part_val, int *part_idx, int *next_rows, int *d_next, int *d_token, hipStream_t st) {
+                        float *part_val, int *part_idx, int *next_rows, int *d_next, int *d_token, int *d_pos,
+                        hipStream_t st) {
     hipLaunchKernelGGL(k_argmax_rows, dim3(ARGMAX_CHUNKS, T), dim3(256), 0, st, logits, V, subset, n_subset,
                        (subset && compact) ? 1 : 0, part_val, part_idx);
     hipLaunchKernelGGL(k_argmax_rows_finish, dim3((T + 63) / 64), dim3(64), 0, st, part_val, part_idx, T, subset, next_rows,
-                       d_next, d_token);
+                       d_next, d_token, d_pos);
 }
 
 void launch_gather_logits(const float *logits, int T, int V, const int *subset, int n_subset, float *out,

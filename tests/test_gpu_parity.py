@@ -513,6 +513,40 @@ def test_verify_step_equals_block_forward_and_decode_steps():
     P.close()
 
 
+def test_short_verify_step_replays_equal_the_eager_sequence(monkeypatch):
+    """Short verify blocks run as one captured sequence per block length. Replays, with eager work and roll-backs
+    between them, must give bit for bit what the same kernels give when launched one by one
+    (EDGEFM_NO_GRAPH=1 at load time): the capture may not freeze any per-call value."""
+    shape = TINY_BF16.with_(max_seq_len=200)
+    w = synth.make_weights(shape)
+    cfg = binding.make_config(shape, max_seq_len=200)
+    captured = binding.Model(cfg, w)
+    monkeypatch.setenv("EDGEFM_NO_GRAPH", "1")
+    eager = binding.Model(cfg, w)
+    monkeypatch.delenv("EDGEFM_NO_GRAPH")
+    rng = np.random.default_rng(17)
+    prompt = synth.make_prompt(shape, 29)
+    for mdl in (captured, eager):
+        mdl.prefill(prompt, want_logits=False)
+    for rnd, m in enumerate((3, 1, 4, 3, 2, 4, 4, 1, 3)):
+        block = rng.integers(0, shape.vocab, size=m).astype(np.int32)
+        na, la = captured.verify_step(block, want_logits=True)
+        nb, lb = eager.verify_step(block, want_logits=True)
+        assert np.array_equal(na, nb) and np.array_equal(la, lb), f"replay {rnd} (m={m})"
+        assert captured.kv_len == eager.kv_len
+        if rnd == 3:                                     # a decode step and a roll-back between replays
+            ta, tb = captured.decode_step(-1)[0], eager.decode_step(-1)[0]
+            assert ta == tb
+            for mdl in (captured, eager):
+                mdl.kv_reset(31)
+        if rnd == 5:                                     # a new candidate set drops the captured sequences
+            ids = np.arange(0, shape.vocab, 3, dtype=np.int32)
+            for mdl in (captured, eager):
+                mdl.set_vocab_subset(ids)
+    captured.close()
+    eager.close()
+
+
 def test_verify_step_7b_width_context_1000():
     """The verify step at the 7B-shaped width (two layers) on top of a 1000-position context."""
     shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
