@@ -115,6 +115,23 @@ int edgefm_decode_step(edgefm_model *m, int32_t token, float *logits_host, int32
 int edgefm_verify_step(edgefm_model *m, const int32_t *token_ids_host, uint32_t n_tokens, float *logits_host,
                        int32_t *next_tokens_host);
 
+/* Arithmetic of the prefill-side GEMMs (Section 3.4 operator table: one operator, several implementations
+ * chosen per deployment; Section 4.1 evaluates 16-bit floating-point inference).  The weights are bf16 or f16
+ * and enter the matrix cores exactly; the choice is how the fp32 activations enter them:
+ *   EDGEFM_PREFILL_F16X2 : as the sum of two f16 terms (two MFMA passes; about fp32 accuracy).  The mode at
+ *                          load time, and the one that agrees with an fp64 evaluation of the model to 2e-3.
+ *   EDGEFM_PREFILL_F16   : rounded to f16 (one MFMA pass, about 1.5 times faster; relative rounding step 2^-11
+ *                          per GEMM input, still eight times finer than bf16 activations).  The rounding of the
+ *                          Q and K projections' input moves attention scores, and a deep network amplifies
+ *                          that: expect 1e-3 .. 1e-2 relative L2 on the final hidden state.
+ * Accumulation, residual stream, normalisation, softmax and RoPE are fp32 in both.  Applies to
+ * edgefm_prefill and to the blocks of edgefm_verify_step that take the GEMM route, from the next call on;
+ * edgefm_decode_step does not use these GEMMs.  The environment variable EDGEFM_PREFILL_TERMS=1 or 2 sets
+ * the mode at load time.  Errors: INVALID_ARG. */
+#define EDGEFM_PREFILL_F16 1
+#define EDGEFM_PREFILL_F16X2 2
+int edgefm_set_prefill_precision(edgefm_model *m, int mode);
+
 /* Release or recycle the KV slot (Section 3.7; Section 3.9 fixed-prefix reuse): keep the first
  * keep_len positions, forget the rest.  keep_len == 0 is a full reset.  Constant time. */
 int edgefm_kv_reset(edgefm_model *m, uint32_t keep_len);

@@ -16,6 +16,7 @@ import numpy as np
 from .buildlib import lib_path
 
 EDGEFM_F16, EDGEFM_BF16 = 1, 2
+EDGEFM_PREFILL_F16, EDGEFM_PREFILL_F16X2 = 1, 2
 EDGEFM_OK = 0
 EDGEFM_ERR_INVALID_ARG, EDGEFM_ERR_ARENA_TOO_SMALL, EDGEFM_ERR_CONTEXT_OVERFLOW = -1, -2, -3
 EDGEFM_ERR_BAD_TOKEN, EDGEFM_ERR_STATE, EDGEFM_ERR_HIP = -4, -5, -6
@@ -27,7 +28,7 @@ EXPORTS = [
     "edgefm_kv_len", "edgefm_model_free", "edgefm_strerror", "edgefm_last_hip_error", "edgefm_debug_kv_read",
     "edgefm_debug_kv_write", "edgefm_debug_kv_fill", "edgefm_debug_set_kv_len", "edgefm_debug_last_hidden",
     "edgefm_debug_launch_op", "edgefm_debug_stage_trace", "edgefm_set_vocab_subset", "edgefm_verify_step",
-    "edgefm_debug_verify_hidden",
+    "edgefm_debug_verify_hidden", "edgefm_set_prefill_precision",
 ]
 
 
@@ -66,6 +67,7 @@ def load_library():
     lib.edgefm_decode_step.argtypes = [m, C.c_int32, C.c_void_p, C.c_void_p]
     lib.edgefm_kv_reset.argtypes = [m, C.c_uint32]
     lib.edgefm_kv_len.argtypes = [m]
+    lib.edgefm_set_prefill_precision.argtypes = [m, C.c_int]
     lib.edgefm_kv_len.restype = C.c_uint32
     lib.edgefm_model_free.argtypes = [m]
     lib.edgefm_model_free.restype = None
@@ -218,6 +220,10 @@ class Model:
         out = np.empty(self.cfg.hidden, dtype=np.float32)
         _check(self.lib.edgefm_debug_verify_hidden(self.h, row, _np_ptr(out)), "edgefm_debug_verify_hidden")
         return out
+
+    def set_prefill_precision(self, mode: int):
+        """edgefm_set_prefill_precision: EDGEFM_PREFILL_F16 or EDGEFM_PREFILL_F16X2."""
+        _check(self.lib.edgefm_set_prefill_precision(self.h, mode), "edgefm_set_prefill_precision")
 
     def set_vocab_subset(self, ids=None):
         """edgefm_set_vocab_subset: ascending candidate token ids (None or empty = whole vocabulary)."""

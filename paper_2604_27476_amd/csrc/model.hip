@@ -14,6 +14,8 @@
 
 using namespace efm;
 
+#define EDGEFM_PREFILL_DEFAULT EDGEFM_PREFILL_F16X2
+
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -171,6 +173,7 @@ struct edgefm_model {
     int32_t *pin_next; // [1]
     int n_part;        // lm_head partial count
     uint32_t n_subset; // candidate tokens of a pruned vocabulary (0 = the whole vocabulary)
+    int act_terms;     // f16 terms per GEMM input activation on the prefill path: 2 (hi + lo) or 1 (rounded)
     bool multi_ok;     // the multi-position decode kernels may be used for short verify blocks
     bool verify_was_gemv;  // which buffers hold the last verify step's hidden states
     std::vector<LayerW> LW;
@@ -350,6 +353,8 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     m->graph_exec = nullptr;
     m->graph_ready = false;
     for (int i = 0; i <= MULTI_MAX; ++i) { m->vgraph[i] = nullptr; m->vgraph_exec[i] = nullptr; }
+    const char *pt = getenv("EDGEFM_PREFILL_TERMS");
+    m->act_terms = (pt && pt[0] == '2') ? 2 : (pt && pt[0] == '1') ? 1 : EDGEFM_PREFILL_DEFAULT;
     const char *ng = getenv("EDGEFM_NO_GRAPH");
     m->use_graph = !(ng && ng[0] == '1');
     m->kv_len = 0;
@@ -540,6 +545,7 @@ int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo), *Qs = m->at<uint16_t>(m->L.Qs),
              *Ohi = m->at<uint16_t>(m->L.Ohi), *Olo = m->at<uint16_t>(m->L.Olo), *Hhi = m->at<uint16_t>(m->L.Hhi),
              *Hlo = m->at<uint16_t>(m->L.Hlo), *Kf = m->at<uint16_t>(m->L.Kf), *Vt = m->at<uint16_t>(m->L.Vt);
+    if (m->act_terms == 1) Alo = Olo = Hlo = nullptr;  // GEMM inputs are their rounded f16 term alone: no second term is made or read
     const size_t q_stride = (size_t)D.max_seq * D.qd();
     const float *rc = m->at<float>(m->L.rope_cos), *rs = m->at<float>(m->L.rope_sin);
     float *ws = m->at<float>(m->L.gemm_ws);
@@ -630,8 +636,8 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
         if (rc != EDGEFM_OK) return rc;
         // every new position needs its prediction: final norm and lm_head as a T-row GEMM against the f16 copy
         uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo);
-        launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);
-        launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
+        launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);  // both terms: the hidden states
+        launch_gemm(D, EPI_BIAS_F32, Ahi, m->act_terms == 2 ? Alo : nullptr, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
                     m->at<float>(m->L.gemm_ws), st);
         launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, false, m->at<float>(m->L.part_val),
                            m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), m->d_pos(), st);
@@ -703,6 +709,12 @@ int edgefm_set_vocab_subset(edgefm_model *m, const int32_t *ids_host, uint32_t n
     }
     m->n_subset = n_ids;
     m->have_prev_token = false;  // a token chosen under the previous candidate set is not carried over
+    return EDGEFM_OK;
+}
+
+int edgefm_set_prefill_precision(edgefm_model *m, int mode) {
+    if (!m || (mode != EDGEFM_PREFILL_F16 && mode != EDGEFM_PREFILL_F16X2)) return EDGEFM_ERR_INVALID_ARG;
+    m->act_terms = mode;
     return EDGEFM_OK;
 }
 

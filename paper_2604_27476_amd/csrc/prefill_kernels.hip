@@ -66,13 +66,13 @@ __device__ __forceinline__ HiLo split2_f16(float a, float b) {
     return HiLo{(uint32_t)ah | ((uint32_t)bh << 16), (uint32_t)al | ((uint32_t)bl << 16)};
 }
 
-// A_hi[t] + A_lo[t] = RMSNorm(X[t]) * gain  (f16 pair)
+// A_hi[t] + A_lo[t] = RMSNorm(X[t]) * gain  (f16 pair; Alo may be null: only the rounded term is kept)
 template <int DT>
 __global__ void k_rmsnorm_rows(const float *__restrict__ X, const uint16_t *__restrict__ gain,
                                uint16_t *__restrict__ Ahi, uint16_t *__restrict__ Alo, int H, float eps) {
     __shared__ float red[32];
     const float *x = X + (size_t)blockIdx.x * H;
-    uint16_t *ah = Ahi + (size_t)blockIdx.x * H, *al = Alo + (size_t)blockIdx.x * H;
+    uint16_t *ah = Ahi + (size_t)blockIdx.x * H, *al = Alo ? Alo + (size_t)blockIdx.x * H : nullptr;
     const int nvec = H >> 3;
     float ss = 0.f;
     for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
@@ -91,7 +91,7 @@ __global__ void k_rmsnorm_rows(const float *__restrict__ X, const uint16_t *__re
         const HiLo s3 = split2_f16(q.z * rstd * g[6], q.w * rstd * g[7]);
         const u32x4 oh = {s0.hi, s1.hi, s2.hi, s3.hi}, ol = {s0.lo, s1.lo, s2.lo, s3.lo};
         *reinterpret_cast<u32x4 *>(ah + 8 * v) = oh;
-        *reinterpret_cast<u32x4 *>(al + 8 * v) = ol;
+        if (al) *reinterpret_cast<u32x4 *>(al + 8 * v) = ol;
     }
 }
 
@@ -191,13 +191,14 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
     }
     u32x4 rah[NA], ral[NA], rb[NB];
     const u32x4 zero = {0u, 0u, 0u, 0u};
+    const bool two = Alo != nullptr;  // a null A_lo: the activations are their rounded f16 term alone
     const int kvo = (tid & 7) * 8;
     auto gload = [&](int k0) {
         const bool kin = k0 + kvo < K;  // K is a multiple of 8
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             rah[i] = (va[i] && kin) ? ld16(Ahi + oa[i] + k0) : zero;
-            ral[i] = (va[i] && kin) ? ld16(Alo + oa[i] + k0) : zero;
+            if (two) ral[i] = (va[i] && kin) ? ld16(Alo + oa[i] + k0) : zero;
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) rb[i] = (vb[i] && kin) ? ld16(W + ob[i] + k0) : zero;
@@ -206,7 +207,7 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             *reinterpret_cast<u32x4 *>(sAh + sa[i]) = rah[i];
-            *reinterpret_cast<u32x4 *>(sAl + sa[i]) = ral[i];
+            if (two) *reinterpret_cast<u32x4 *>(sAl + sa[i]) = ral[i];
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) *reinterpret_cast<u32x4 *>(sB + sb[i]) = rb[i];
@@ -234,7 +235,7 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
             for (int t = 0; t < TM; ++t) {
                 const int ao = (wm * 32 * TM + t * 32 + fr) * LDK + ks * 16 + fk;
                 fah[t] = *reinterpret_cast<const u32x4 *>(sAh + ao);
-                fal[t] = *reinterpret_cast<const u32x4 *>(sAl + ao);
+                if (two) fal[t] = *reinterpret_cast<const u32x4 *>(sAl + ao);
             }
 #pragma unroll
             for (int t = 0; t < TN; ++t)
@@ -243,10 +244,12 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(fah[a], fb[b], acc[a][b]);
+            if (two) {
 #pragma unroll
-            for (int a = 0; a < TM; ++a)
+                for (int a = 0; a < TM; ++a)
 #pragma unroll
-                for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(fal[a], fb[b], acc[a][b]);
+                    for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(fal[a], fb[b], acc[a][b]);
+            }
         }
         __syncthreads();
         if (kt + 1 < nk) {
@@ -273,7 +276,7 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
                         uint16_t h, l;
                         split_f16(g / (1.0f + expf(-g)) * u, h, l);
                         ohi[(size_t)m * N + j] = h;
-                        olo[(size_t)m * N + j] = l;
+                        if (olo) olo[(size_t)m * N + j] = l;
                     }
                 }
             } else {
@@ -307,7 +310,7 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 constexpr int PK = 32;                     // k-tile depth
 constexpr int P_STAGES = 3;
 constexpr int P_BN = 256;                  // tile columns; tile rows are 64 WM
-constexpr int pipe_stage_elems(int wm) { return (2 * 64 * wm + P_BN) * PK; }  // A_hi | A_lo | B, f16 elements per stage
+constexpr int pipe_stage_elems(int wm, int terms) { return (terms * 64 * wm + P_BN) * PK; }  // A_hi | (A_lo) | B, f16 elements per stage
 constexpr int PIPE_MAX_SPLITS = 8;          // k-slices per tile at most
 constexpr int PIPE_MIN_SLICE_TILES = 16;    // k-tiles per slice at least (keeps the tile prologue and epilogue small)
 static_assert((size_t)256 * P_BN * 4 * 256 <= GEMM_WS_BYTES, "a split round (slices x tiles <= CUs) has to fit the workspace");
@@ -343,15 +346,16 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));
 }
 
-template <int BDT, int EPI, int WM>
+template <int BDT, int EPI, int WM, int TERMS>
 __global__ void __launch_bounds__(512)
 k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
             int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
             uint16_t *__restrict__ olo, PipeRange R) {
     constexpr int TM = 2, TN = WM, WN = 32 * TN, WNW = 8 / WM;  // wave tile 64 x WN, waves WM x WNW
-    constexpr int BM = 64 * WM, STAGE_ELEMS = pipe_stage_elems(WM);
+    constexpr int BM = 64 * WM, STAGE_ELEMS = pipe_stage_elems(WM, TERMS);
+    constexpr int B_AT = TERMS * BM * PK;  // element offset of the B tile inside a stage
     static_assert(WNW * WN == P_BN, "the waves of a row have to cover the tile columns");
-    extern __shared__ __attribute__((aligned(1024))) uint16_t ring[];  // P_STAGES x (A_hi, A_lo, B)
+    extern __shared__ __attribute__((aligned(1024))) uint16_t ring[];  // P_STAGES x (A_hi, A_lo if TERMS == 2, B)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WNW, wn = wave % WNW;
@@ -370,7 +374,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         const int kbeg = (int)((long long)split * nk_all / R.k_splits);
         nk = (int)((long long)(split + 1) * nk_all / R.k_splits) - kbeg;
         Ahi += (size_t)kbeg * PK;
-        Alo += (size_t)kbeg * PK;
+        if constexpr (TERMS == 2) Alo += (size_t)kbeg * PK;
         W += (size_t)kbeg * PK;
     }
     auto brow = [&](int r) -> int {  // global weight row of B-tile row r (clamped inside the matrix)
@@ -385,7 +389,8 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     // DMA plan: one instruction moves 16 rows x 64 B.  Wave w issues, per stage, instructions A_I w .. A_I w + A_I - 1
     // of the two A tiles and 2w, 2w + 1 of the B tile.  Lane l of an instruction covers row R0 + l/4, slot l%4,
     // i.e. logical chunk (l%4) ^ ((row >> 1) & 3).
-    // With WM = 1 the two A tiles are 4 instructions each: waves 0-3 take one of A_hi, waves 4-7 one of A_lo.
+    // With WM = 1 the two A tiles are 4 instructions each: waves 0-3 take one of A_hi, waves 4-7 one of A_lo
+    // (none with TERMS = 1).
     constexpr int A_I = BM >= 128 ? BM / 128 : 1, B_I = P_BN / 128;
     constexpr bool A_SPLIT = BM < 128;  // a wave loads from one of the two A tiles only
     uint32_t ga[A_I], gb[B_I];  // byte offsets of this lane's chunk at k0 = 0 (A_hi and A_lo share ga)
@@ -410,16 +415,16 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         const int k0 = kt * PK;
         if constexpr (A_SPLIT) {
             if (wave < 4) lds_dma16(Ahi + k0, ga[0], st + la[0]);
-            else lds_dma16(Alo + k0, ga[0], st + BM * PK * 2 + la[0]);
+            else if constexpr (TERMS == 2) lds_dma16(Alo + k0, ga[0], st + BM * PK * 2 + la[0]);
         } else {
 #pragma unroll
             for (int i = 0; i < A_I; ++i) {
                 lds_dma16(Ahi + k0, ga[i], st + la[i]);
-                lds_dma16(Alo + k0, ga[i], st + BM * PK * 2 + la[i]);
+                if constexpr (TERMS == 2) lds_dma16(Alo + k0, ga[i], st + BM * PK * 2 + la[i]);
             }
         }
 #pragma unroll
-        for (int i = 0; i < B_I; ++i) lds_dma16(W + k0, gb[i], st + 2 * BM * PK * 2 + lb[i]);
+        for (int i = 0; i < B_I; ++i) lds_dma16(W + k0, gb[i], st + B_AT * 2 + lb[i]);
     };
 
     f32x16 acc[TM][TN];
@@ -442,12 +447,12 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
             const int r = wm * 64 + t * 32 + fr;
             const int off = r * PK + (((ks * 2 + hf) ^ ((r >> 1) & 3)) << 3);
             f.ah[t] = *reinterpret_cast<const u32x4 *>(st + off);
-            f.al[t] = *reinterpret_cast<const u32x4 *>(st + BM * PK + off);
+            if constexpr (TERMS == 2) f.al[t] = *reinterpret_cast<const u32x4 *>(st + BM * PK + off);
         }
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             const int r = wn * WN + t * 32 + fr;
-            f.b[t] = *reinterpret_cast<const u32x4 *>(st + 2 * BM * PK + r * PK +
+            f.b[t] = *reinterpret_cast<const u32x4 *>(st + B_AT + r * PK +
                                                       (((ks * 2 + hf) ^ ((r >> 1) & 3)) << 3));
         }
     };
@@ -456,10 +461,12 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         for (int a = 0; a < TM; ++a)
 #pragma unroll
             for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(f.ah[a], f.b[b], acc[a][b]);
+        if constexpr (TERMS == 2) {
 #pragma unroll
-        for (int a = 0; a < TM; ++a)
+            for (int a = 0; a < TM; ++a)
 #pragma unroll
-            for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(f.al[a], f.b[b], acc[a][b]);
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(f.al[a], f.b[b], acc[a][b]);
+        }
     };
     static_assert(PK == 32 && P_STAGES == 3, "the schedule below is written for two k-steps per tile and a ring of three");
     // Schedule: the eight waves form two groups of four (one wave of each group per SIMD) that alternate
@@ -476,13 +483,16 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     Frag f0, f1;
     issue(0);
     if (nk > 1) issue(1);
-    constexpr int NI = (A_SPLIT ? 1 : 2 * A_I) + B_I;  // this wave's LDS-DMA instructions per k-tile
+    // this wave's LDS-DMA instructions per k-tile (with WM = 1 and one term, waves 4-7 issue one fewer)
+    constexpr int NI = (A_SPLIT ? 1 : TERMS * A_I) + B_I;
+    constexpr bool NI_BY_WAVE = A_SPLIT && TERMS == 1;
     static_assert(NI == 6 || NI == 4 || NI == 3, "the vmcnt immediates below are written for these shapes");
 #define WAIT_ALL_BUT_ONE_TILE(extra)                                                        \
     do {                                                                                    \
         if constexpr (NI == 6) asm volatile("s_waitcnt vmcnt(6)" extra ::: "memory");       \
         else if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(4)" extra ::: "memory");  \
-        else asm volatile("s_waitcnt vmcnt(3)" extra ::: "memory");                         \
+        else if (!NI_BY_WAVE || wave < 4) asm volatile("s_waitcnt vmcnt(3)" extra ::: "memory"); \
+        else asm volatile("s_waitcnt vmcnt(2)" extra ::: "memory");                         \
     } while (0)
     if (nk > 1) WAIT_ALL_BUT_ONE_TILE("");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -557,7 +567,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
                     uint16_t h, l;
                     split_f16(g / (1.0f + expf(-g)) * u, h, l);
                     ohi[(size_t)m * N + j] = h;
-                    olo[(size_t)m * N + j] = l;
+                    if (olo) olo[(size_t)m * N + j] = l;
                 }
             } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
@@ -568,7 +578,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
                         uint16_t h, l;
                         split_f16(g / (1.0f + expf(-g)) * u, h, l);
                         ohi[(size_t)m * N + j] = h;
-                        olo[(size_t)m * N + j] = l;
+                        if (olo) olo[(size_t)m * N + j] = l;
                     }
                 }
             } else {
@@ -623,7 +633,7 @@ k_splitk_finish(PipeRange R, int T, int N, const uint16_t *__restrict__ bias, fl
                 uint16_t h, l;
                 split_f16(g[e] / (1.0f + expf(-g[e])) * u[e], h, l);
                 ohi[(size_t)m * N + j + e] = h;
-                olo[(size_t)m * N + j + e] = l;
+                if (olo) olo[(size_t)m * N + j + e] = l;
             }
         } else {
             const int n = nb * NOUT + o;
@@ -929,7 +939,7 @@ k_flash_attn(const uint16_t *__restrict__ Qs, size_t q_stride, const uint16_t *_
                 const HiLo s1 = split2_f16(oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
                 const u32x2 vh = {s0.hi, s1.hi}, vl = {s0.lo, s1.lo};
                 *reinterpret_cast<u32x2 *>(oh + dd) = vh;
-                *reinterpret_cast<u32x2 *>(ol + dd) = vl;
+                if (Olo) *reinterpret_cast<u32x2 *>(ol + dd) = vl;
             }
     }
 }
@@ -973,7 +983,7 @@ k_flash_merge(const float *__restrict__ part, int n_splits, int T, int p0, uint1
                 acc += *reinterpret_cast<const f32x4 *>(rec0 + (size_t)sp * (128 * (D + 2)) + 256 + ((size_t)dg * 128 + q) * 4) * w[sp];
         const HiLo s0 = split2_f16(acc[0] * inv, acc[1] * inv), s1 = split2_f16(acc[2] * inv, acc[3] * inv);
         *reinterpret_cast<u32x2 *>(oh + 4 * dg) = u32x2{s0.hi, s1.hi};
-        *reinterpret_cast<u32x2 *>(ol + 4 * dg) = u32x2{s0.lo, s1.lo};
+        if (Olo) *reinterpret_cast<u32x2 *>(ol + 4 * dg) = u32x2{s0.lo, s1.lo};
     }
 }
 
@@ -1097,15 +1107,17 @@ static bool gemm_pipe_enabled() {
     if (state < 0) {
         const char *e = getenv("EDGEFM_GEMM");
         bool ok = !(e && e[0] == 't');
-#define PIPE_ATTR(BDT, EPI, WM)                                                                                \
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pipe<BDT, EPI, WM>),                \
+#define PIPE_ATTR1(BDT, EPI, WM, TERMS)                                                                        \
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pipe<BDT, EPI, WM, TERMS>),         \
                                    hipFuncAttributeMaxDynamicSharedMemorySize,                                 \
-                                   P_STAGES * pipe_stage_elems(WM) * 2) == hipSuccess;
+                                   P_STAGES * pipe_stage_elems(WM, TERMS) * 2) == hipSuccess;
+#define PIPE_ATTR(BDT, EPI, WM) PIPE_ATTR1(BDT, EPI, WM, 1) PIPE_ATTR1(BDT, EPI, WM, 2)
 #define PIPE_ATTR_EPI(BDT, WM) PIPE_ATTR(BDT, EPI_SWIGLU, WM) PIPE_ATTR(BDT, EPI_RESID, WM) PIPE_ATTR(BDT, EPI_BIAS_F32, WM)
         PIPE_ATTR_EPI(DT_BF16, 4) PIPE_ATTR_EPI(DT_BF16, 2) PIPE_ATTR_EPI(DT_BF16, 1)
         PIPE_ATTR_EPI(DT_F16, 4) PIPE_ATTR_EPI(DT_F16, 2) PIPE_ATTR_EPI(DT_F16, 1)
 #undef PIPE_ATTR_EPI
 #undef PIPE_ATTR
+#undef PIPE_ATTR1
         state = ok ? 1 : 0;
     }
     return state == 1;
@@ -1121,19 +1133,19 @@ static int device_cu_count() {
     return n;
 }
 
-template <int BDT, int WM>
-static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+template <int BDT, int WM, int TERMS>
+static void pipe_launch_terms(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                         const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
                         hipStream_t st) {
     const int per_xcd = (R.n_tiles * R.k_splits + N_XCD - 1) / N_XCD;
     const dim3 grid(per_xcd * N_XCD), block(512);
-    const size_t lds = (size_t)P_STAGES * pipe_stage_elems(WM) * 2;
+    const size_t lds = (size_t)P_STAGES * pipe_stage_elems(WM, TERMS) * 2;
     if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU, WM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     else if (epi == EPI_RESID)
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID, WM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     else
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32, WM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     if (R.k_splits > 1) {
         const dim3 fgrid(R.n_tiles, R.bm / FIN_ROWS);
         if (epi == EPI_SWIGLU)
@@ -1143,6 +1155,15 @@ static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const
         else
             hipLaunchKernelGGL((k_splitk_finish<BDT, EPI_BIAS_F32>), fgrid, dim3(256), 0, st, R, T, N, bias, outf, ohi, olo);
     }
+}
+
+// A null A_lo selects the one-term kernels: the activations are their rounded f16 term alone.
+template <int BDT, int WM>
+static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
+                        const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
+                        hipStream_t st) {
+    if (Alo) pipe_launch_terms<BDT, WM, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, st);
+    else pipe_launch_terms<BDT, WM, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, st);
 }
 
 // Full rounds of tiles (one per CU) in one launch; the tiles of a partly filled last round are cut along K

@@ -593,6 +593,55 @@ def _get_7b_l2(shape):
     return _cache["p"]
 
 
+F16_MODE_TOL = 1e-2   # one-term activations at depth 2: measured 1e-3 .. 3e-3, against 1e-5 in the default mode
+
+
+def test_prefill_one_term_activation_mode_7b_width():
+    """EDGEFM_PREFILL_F16 (GEMM inputs rounded to one f16 term) on every tile shape of the prefill GEMMs:
+    64-row tiles (T = 40), 128- and 256-row tiles (T = 500: O / down / QKV on 128, gate/up on 256) and 256-row
+    tiles with cut last rounds (T = 1024).  The mode is looser than the library's parity bar by design, so it is
+    held to its own documented bound against the oracle; switching back must restore the default mode's result
+    bit for bit, and the mode must change nothing but rounding (K/V rows within a rounding step)."""
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    g, o = P.gm, P.om
+    for T in (40, 500, 1024):
+        prompt = synth.make_prompt(shape, T, seed=synth.SEED_PROMPT + 31 * T)
+        o.kv_reset(0)
+        ref = o.prefill(prompt)
+        g.kv_reset(0)
+        n2, l2 = g.prefill(prompt)
+        h2 = g.last_hidden().copy()
+        kv2 = g.kv_read(1, T - 1)
+        g.kv_reset(0)
+        g.set_prefill_precision(binding.EDGEFM_PREFILL_F16)
+        n1, l1 = g.prefill(prompt)
+        h1 = g.last_hidden().copy()
+        kv1 = g.kv_read(1, T - 1)
+        g.kv_reset(0)
+        g.set_prefill_precision(binding.EDGEFM_PREFILL_F16X2)
+        n2b, l2b = g.prefill(prompt)
+        e2, e1 = rel_l2(h2, ref["hidden"][-1]), rel_l2(h1, ref["hidden"][-1])
+        print(f"T={T}: two terms {e2:.2e}, one term {e1:.2e} (logits {rel_l2(l1, ref['logits']):.2e})", flush=True)
+        assert e2 <= REL_TOL
+        assert e2 < e1 <= F16_MODE_TOL and rel_l2(l1, ref["logits"]) <= F16_MODE_TOL
+        assert n2b == n2 and np.array_equal(l2b, l2)
+        for a, b in zip(kv1, kv2):                       # layer 1 rows: same values up to the cache type's rounding
+            fa = synth.from_bits(a, shape.kv_dtype).astype(np.float64)
+            fb = synth.from_bits(b, shape.kv_dtype).astype(np.float64)
+            assert np.abs(fa - fb).max() <= 0.03 * max(1.0, np.abs(fb).max())
+    # a verify block on the GEMM route in the one-term mode, then back
+    g.set_prefill_precision(binding.EDGEFM_PREFILL_F16)
+    block = np.random.default_rng(8).integers(0, shape.vocab, size=8).astype(np.int32)
+    ob = o.forward(block, logits="all")
+    nxt, lg = g.verify_step(block, want_logits=True)
+    assert rel_l2(lg, ob["logits"]) <= F16_MODE_TOL
+    g.set_prefill_precision(binding.EDGEFM_PREFILL_F16X2)
+    with pytest.raises(binding.EdgefmError) as e:
+        g.set_prefill_precision(3)
+    assert e.value.status == binding.EDGEFM_ERR_INVALID_ARG
+
+
 def test_long_prefill_7b_width_two_layers():
     """Prefill GEMMs and flash attention at T = 2048 on the 7B-shaped width (depth 2), then the VLM-shaped
     request: 1024 embedding rows + 64 tokens in one prefill and an 8-token greedy decode (configs[4])."""
