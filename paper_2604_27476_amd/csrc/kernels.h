@@ -130,9 +130,23 @@ enum GemmEpi { EPI_BIAS_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 //   EPI_SWIGLU  : W16 is [2 I, K] (gate | up), out_hi + out_lo [T,I] = silu(C_gate) * C_up, N = I
 // ws: GEMM_WS_BYTES of scratch for the k-slices of split tiles (null: tiles are never split)
 constexpr size_t GEMM_WS_BYTES = (size_t)64 << 20;
+// Which tiles a GEMM launch covers: tiles [tile_begin, tile_begin + n_tiles) of the n_mt x n_nt grid (tile rows
+// bm) in grouped order, each cut into k_splits slices along K.  With k_splits > 1 every slice leaves its partial
+// tile in ws[(slice * n_tiles + local tile)][bm][256] and the slices are added up in slice order afterwards.
+struct PipeRange {
+    int n_mt, n_nt, tile_begin, n_tiles, k_splits, bm;
+    int wn_out;  // SwiGLU outputs per wave tile: the tile's columns are wn_out gate rows, wn_out up rows, ...
+    float *ws;
+};
+// pending (EPI_RESID only, may be null): the sum of the k-slices of split tiles is left to the caller, who
+// passes *pending to launch_resid_norm_rows before ws is used again; k_splits == 1 there means nothing is left.
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
                  int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
-                 hipStream_t st);
+                 PipeRange *pending, hipStream_t st);
+// X[t] += the k-slices a residual GEMM left pending;  A_hi[t] + A_lo[t] <- RMSNorm(X[t]) * gain  (gain null: the
+// sum alone; A_lo null: the rounded term alone).  X is [T, D.H].
+void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pending, const uint16_t *gain,
+                            uint16_t *Ahi, uint16_t *Alo, hipStream_t st);
 // RoPE + cache write for positions p0..p0+T-1; Qs[0][t] + Qs[1][t] = RoPE(q_t)
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
                     uint16_t *Qs, size_t q_stride, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);

@@ -529,9 +529,10 @@ int check_append(const edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
 
 // Embed T = n_embeds + n_tokens new positions and run them through every layer (Eq. 3), appending their K/V at
 // positions kv_len ...  Leaves the residual stream of the new positions in X.  With last_row_only the last
-// layer's MLP runs on the last position alone (nothing else reads the others).
+// layer's MLP runs on the last position alone (nothing else reads the others); otherwise the rows of X come out
+// normalised with final_gain as well (A_hi + A_lo, both terms), unless that is null.
 int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, const void *embeds_dev, uint32_t n_embeds,
-                   bool last_row_only) {
+                   bool last_row_only, const uint16_t *final_gain) {
     const Dims &D = m->D;
     const int T = (int)(n_tokens + n_embeds), p0 = (int)m->kv_len, ctx = p0 + T, ctx_pad = (ctx + 63) / 64 * 64;
     hipStream_t st = m->stream;
@@ -551,27 +552,32 @@ int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     float *ws = m->at<float>(m->L.gemm_ws);
     launch_embed_rows(D, m->at<uint16_t>(m->L.embed), static_cast<const uint16_t *>(embeds_dev), (int)n_embeds, tok,
                       (int)n_tokens, X, st);
+    // The sums of the split O and down GEMMs run fused with the normalisation that follows each of them.
+    PipeRange pend;
+    launch_rmsnorm_rows(D, X, m->LW[0].attn_norm, T, Ahi, Alo, st);
     for (int l = 0; l < D.L; ++l) {
         const LayerW &W = m->LW[l];
         const edgefm_model::PrefillW &P = m->PW[l];
-        launch_rmsnorm_rows(D, X, W.attn_norm, T, Ahi, Alo, st);
         launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, D.qkv_bias ? W.bqkv : nullptr, QKV, nullptr,
-                    nullptr, ws, st);
+                    nullptr, ws, nullptr, st);
         launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, m->kc(l), m->vc(l), st);
         launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
         launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, m->at<float>(m->L.flash_part), st);
-        launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, st);
+        launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, &pend, st);
         if (l == D.L - 1 && last_row_only) {
             // Nothing reads the last layer's MLP output except the final norm of the last position (the
             // cache rows of every layer are complete at this point): one row through the decode kernels.
+            launch_resid_norm_rows(D, X, T, pend, nullptr, nullptr, nullptr, st);
             float *xl = X + (size_t)(T - 1) * D.H, *h = m->at<float>(m->L.h);
             launch_gateup(D, m->G, W, xl, h, st);
             launch_gemv_resid(D, m->G, W.w_down, D.I, h, xl, st);
             break;
         }
-        launch_rmsnorm_rows(D, X, W.mlp_norm, T, Ahi, Alo, st);
-        launch_gemm(D, EPI_SWIGLU, Ahi, Alo, P.w_gate_up, T, D.I, D.H, nullptr, nullptr, Hhi, Hlo, ws, st);
-        launch_gemm(D, EPI_RESID, Hhi, Hlo, P.w_down, T, D.H, D.I, nullptr, X, nullptr, nullptr, ws, st);
+        launch_resid_norm_rows(D, X, T, pend, W.mlp_norm, Ahi, Alo, st);
+        launch_gemm(D, EPI_SWIGLU, Ahi, Alo, P.w_gate_up, T, D.I, D.H, nullptr, nullptr, Hhi, Hlo, ws, nullptr, st);
+        launch_gemm(D, EPI_RESID, Hhi, Hlo, P.w_down, T, D.H, D.I, nullptr, X, nullptr, nullptr, ws, &pend, st);
+        if (l + 1 < D.L) launch_resid_norm_rows(D, X, T, pend, m->LW[l + 1].attn_norm, Ahi, Alo, st);
+        else launch_resid_norm_rows(D, X, T, pend, final_gain, Ahi, m->at<uint16_t>(m->L.Alo), st);  // both terms: the hidden states
     }
     return EDGEFM_OK;
 }
@@ -586,7 +592,7 @@ int edgefm_prefill(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     const Dims &D = m->D;
     const int T = (int)(n_tokens + n_embeds), ctx = (int)m->kv_len + T;
     hipStream_t st = m->stream;
-    rc = enqueue_layers(m, tok_host, n_tokens, embeds_dev, n_embeds, true);
+    rc = enqueue_layers(m, tok_host, n_tokens, embeds_dev, n_embeds, true, nullptr);
     if (rc != EDGEFM_OK) return rc;
     // only the last position needs logits: final norm + lm_head as a GEMV on that row
     launch_lmhead(D, m->G, m->lm(), m->at<uint16_t>(m->L.final_norm), m->at<float>(m->L.X) + (size_t)(T - 1) * D.H,
@@ -632,13 +638,13 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
             enqueue_verify_gemv(m, T, st);
         }
     } else {
-        rc = enqueue_layers(m, tok_host, n_tokens, nullptr, 0, false);
+        // every new position needs its prediction: final norm (with the last layer's sum) and lm_head as a T-row
+        // GEMM against the f16 copy
+        rc = enqueue_layers(m, tok_host, n_tokens, nullptr, 0, false, m->at<uint16_t>(m->L.final_norm));
         if (rc != EDGEFM_OK) return rc;
-        // every new position needs its prediction: final norm and lm_head as a T-row GEMM against the f16 copy
         uint16_t *Ahi = m->at<uint16_t>(m->L.Ahi), *Alo = m->at<uint16_t>(m->L.Alo);
-        launch_rmsnorm_rows(D, m->at<float>(m->L.X), m->at<uint16_t>(m->L.final_norm), T, Ahi, Alo, st);  // both terms: the hidden states
         launch_gemm(D, EPI_BIAS_F32, Ahi, m->act_terms == 2 ? Alo : nullptr, m->at<uint16_t>(m->L.p_lm), T, D.V, D.H, nullptr, vlogits, nullptr, nullptr,
-                    m->at<float>(m->L.gemm_ws), st);
+                    m->at<float>(m->L.gemm_ws), nullptr, st);
         launch_argmax_rows(vlogits, T, D.V, subset, (int)m->n_subset, false, m->at<float>(m->L.part_val),
                            m->at<int>(m->L.part_idx), m->at<int>(m->L.vnext), m->d_next(), m->d_token(), m->d_pos(), st);
         if (logits_host && subset) {

@@ -311,18 +311,11 @@ constexpr int PK = 32;                     // k-tile depth
 constexpr int P_STAGES = 3;
 constexpr int P_BN = 256;                  // tile columns; tile rows are 64 WM
 constexpr int pipe_stage_elems(int wm, int terms) { return (terms * 64 * wm + P_BN) * PK; }  // A_hi | (A_lo) | B, f16 elements per stage
-constexpr int PIPE_MAX_SPLITS = 8;          // k-slices per tile at most
-constexpr int PIPE_MIN_SLICE_TILES = 16;    // k-tiles per slice at least (keeps the tile prologue and epilogue small)
-static_assert((size_t)256 * P_BN * 4 * 256 <= GEMM_WS_BYTES, "a split round (slices x tiles <= CUs) has to fit the workspace");
+constexpr int PIPE_MAX_SPLITS = 8;          // k-slices per tile at most (twice that for the 64-row tiles)
+constexpr int PIPE_MIN_SLICE_TILES = 16;    // k-tiles per slice at least (half that for the 64-row tiles)
+constexpr float PIPE_UNIT_OVERHEAD = 8.f;   // prologue, epilogue and slice sum of one work unit, in k-tiles
+static_assert((size_t)256 * P_BN * 4 * 256 <= GEMM_WS_BYTES, "one round of 256-row work units has to fit the workspace");
 
-// Which tiles a launch covers: tiles [tile_begin, tile_begin + n_tiles) of the n_mt x n_nt grid in grouped
-// order, each cut into k_splits slices along K.  With k_splits > 1 every slice leaves its partial tile in
-// ws[(slice * n_tiles + local tile)][bm][256] and k_splitk_finish adds the slices up in a fixed order.
-struct PipeRange {
-    int n_mt, n_nt, tile_begin, n_tiles, k_splits, bm;
-    int wn_out;  // SwiGLU outputs per wave tile: the tile's columns are wn_out gate rows, wn_out up rows, ...
-    float *ws;
-};
 __device__ __forceinline__ void pipe_tile(const PipeRange &R, int tl, int &mt, int &nb) {
     const int v = R.tile_begin + tl;
     const int gsz = GROUP_M * R.n_nt, gid = v / gsz, first_m = gid * GROUP_M;
@@ -547,6 +540,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = wm * 64 + a * 32 + 8 * (i >> 2) + 4 * hf + (i & 3);
+                if (m0 + row >= T) continue;  // the sum reads the rows of the block only
 #pragma unroll
                 for (int b = 0; b < TN; ++b) wt[row * P_BN + wn * WN + b * 32 + fr] = acc[a][b][i] * UNSCALE;
             }
@@ -646,6 +640,68 @@ k_splitk_finish(PipeRange R, int T, int N, const uint16_t *__restrict__ bias, fl
                 else outf[(size_t)m * N + n + e] = c[e] + (bias ? up1<BDT>(bias[n + e]) : 0.f);
             }
         }
+    }
+}
+
+// The sum of a split residual GEMM fused with the normalisation that follows it: for row t,
+//   X[t] += sum over the k-slices (slice order) of the split tiles;  A_hi[t] + A_lo[t] <- RMSNorm(X[t]) * gain.
+// Tiles of the same GEMM that were not split have already been added to X by the GEMM's own epilogue.  One
+// workgroup per row (256 threads, or 1024 for short blocks, where the rows are few and the slices many); with
+// k_splits <= 1 this is the plain row normalisation, with a null gain the plain sum.
+template <int DT>
+__global__ void __launch_bounds__(1024)
+k_resid_norm_rows(float *__restrict__ X, PipeRange R, const uint16_t *__restrict__ gain, uint16_t *__restrict__ Ahi,
+                  uint16_t *__restrict__ Alo, int H, float eps) {
+    __shared__ float red[32];
+    const int t = blockIdx.x;
+    float *x = X + (size_t)t * H;
+    const int nvec = H >> 2;
+    float ss = 0.f;
+    if (R.k_splits > 1) {
+        // virtual index of the row's tile in column tile 0 and its step per column tile (grouped order, see pipe_tile)
+        const int mt = t / R.bm, r = t - mt * R.bm;
+        const int gid = mt / GROUP_M, first_m = gid * GROUP_M, gm = min(GROUP_M, R.n_mt - first_m);
+        const int v0 = gid * GROUP_M * R.n_nt + (mt - first_m);
+        const size_t slice = (size_t)R.n_tiles * (R.bm * P_BN);
+        for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+            const int c = 4 * v, nb = c / P_BN, o = c - nb * P_BN;
+            const int tl = v0 + nb * gm - R.tile_begin;
+            f32x4 xv = *reinterpret_cast<const f32x4 *>(x + c);
+            if (tl >= 0 && tl < R.n_tiles) {
+                const float *wt = R.ws + (size_t)tl * (R.bm * P_BN) + r * P_BN + o;
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+                int sl = 0;
+                for (; sl + 4 <= R.k_splits; sl += 4) {  // four loads in flight, added in slice order
+                    const f32x4 p0 = *reinterpret_cast<const f32x4 *>(wt + (sl + 0) * slice);
+                    const f32x4 p1 = *reinterpret_cast<const f32x4 *>(wt + (sl + 1) * slice);
+                    const f32x4 p2 = *reinterpret_cast<const f32x4 *>(wt + (sl + 2) * slice);
+                    const f32x4 p3 = *reinterpret_cast<const f32x4 *>(wt + (sl + 3) * slice);
+                    sum = (((sum + p0) + p1) + p2) + p3;
+                }
+                for (; sl < R.k_splits; ++sl) sum += *reinterpret_cast<const f32x4 *>(wt + sl * slice);
+                xv += sum;
+                *reinterpret_cast<f32x4 *>(x + c) = xv;
+            }
+            ss += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
+        }
+    } else {
+        for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+            const f32x4 xv = *reinterpret_cast<const f32x4 *>(x + 4 * v);
+            ss += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
+        }
+    }
+    if (!gain) return;
+    ss = block_sum(ss, red);
+    const float rstd = 1.0f / sqrtf(ss / (float)H + eps);
+    uint16_t *ah = Ahi + (size_t)t * H, *al = Alo ? Alo + (size_t)t * H : nullptr;
+    // each thread reads back the values it wrote itself
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        const f32x4 xv = *reinterpret_cast<const f32x4 *>(x + 4 * v);
+        const uint16_t *gp = gain + 4 * v;
+        const HiLo s0 = split2_f16(xv[0] * rstd * up1<DT>(gp[0]), xv[1] * rstd * up1<DT>(gp[1]));
+        const HiLo s1 = split2_f16(xv[2] * rstd * up1<DT>(gp[2]), xv[3] * rstd * up1<DT>(gp[3]));
+        *reinterpret_cast<u32x2 *>(ah + 4 * v) = u32x2{s0.hi, s1.hi};
+        if (al) *reinterpret_cast<u32x2 *>(al + 4 * v) = u32x2{s0.lo, s1.lo};
     }
 }
 
@@ -1135,8 +1191,8 @@ static int device_cu_count() {
 
 template <int BDT, int WM, int TERMS>
 static void pipe_launch_terms(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
-                        const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
-                        hipStream_t st) {
+                              const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
+                              bool defer_sum, hipStream_t st) {
     const int per_xcd = (R.n_tiles * R.k_splits + N_XCD - 1) / N_XCD;
     const dim3 grid(per_xcd * N_XCD), block(512);
     const size_t lds = (size_t)P_STAGES * pipe_stage_elems(WM, TERMS) * 2;
@@ -1146,7 +1202,7 @@ static void pipe_launch_terms(int epi, const uint16_t *Ahi, const uint16_t *Alo,
         hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
     else
         hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
-    if (R.k_splits > 1) {
+    if (R.k_splits > 1 && !defer_sum) {
         const dim3 fgrid(R.n_tiles, R.bm / FIN_ROWS);
         if (epi == EPI_SWIGLU)
             hipLaunchKernelGGL((k_splitk_finish<BDT, EPI_SWIGLU>), fgrid, dim3(256), 0, st, R, T, N, bias, outf, ohi, olo);
@@ -1161,42 +1217,54 @@ static void pipe_launch_terms(int epi, const uint16_t *Ahi, const uint16_t *Alo,
 template <int BDT, int WM>
 static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                         const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, const PipeRange &R,
-                        hipStream_t st) {
-    if (Alo) pipe_launch_terms<BDT, WM, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, st);
-    else pipe_launch_terms<BDT, WM, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, st);
+                        bool defer_sum, hipStream_t st) {
+    if (Alo) pipe_launch_terms<BDT, WM, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, defer_sum, st);
+    else pipe_launch_terms<BDT, WM, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, defer_sum, st);
 }
 
 // Full rounds of tiles (one per CU) in one launch; the tiles of a partly filled last round are cut along K
 // instead, so that the round is short and busy on every CU, and their slices meet in the workspace.
 template <int BDT, int WM>
 static bool pipe_plan(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
-                      const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, hipStream_t st) {
+                      const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, PipeRange *pending,
+                      hipStream_t st) {
     constexpr int BM = 64 * WM;
     const int n_mt = (T + BM - 1) / BM;
     const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
     const int n_cu = std::min(device_cu_count(), 256), tiles = n_mt * n_nt, nk = K / PK;
     const int rem = tiles % n_cu, full = tiles - rem;
+    // k-slices for the tiles of the last round: the count that minimises rounds x (k-tiles per unit + overhead),
+    // within the workspace.  With about a round's worth of tiles or less this is the largest count that still
+    // fits one round; with the 148 gate/up column tiles of a 64-row block it is three (two short rounds).
     int splits = 1;
-    if (rem > 0 && ws) splits = std::min(std::min(n_cu / rem, WM == 1 ? 2 * PIPE_MAX_SPLITS : PIPE_MAX_SPLITS), nk / PIPE_MIN_SLICE_TILES);
+    if (rem > 0 && ws) {
+        const int kmax = std::min(WM == 1 ? 2 * PIPE_MAX_SPLITS : PIPE_MAX_SPLITS, nk / (WM == 1 ? PIPE_MIN_SLICE_TILES / 2 : PIPE_MIN_SLICE_TILES));
+        auto cost = [&](int k) { return (float)((rem * k + n_cu - 1) / n_cu) * ((float)nk / (float)k + PIPE_UNIT_OVERHEAD); };
+        for (int k = 2; k <= kmax; ++k)
+            if ((size_t)rem * k * BM * P_BN * 4 <= GEMM_WS_BYTES && cost(k) < 0.97f * cost(splits)) splits = k;
+    }
     if (splits < 2) {
         if (tiles * 2 < n_cu) return false;  // fewer than half of the CUs would work: leave it to the tile kernels
-        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, tiles, 1, BM, 16 * WM, nullptr}, st);
+        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, tiles, 1, BM, 16 * WM, nullptr}, false, st);
         return true;
     }
     if (full > 0)
-        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, full, 1, BM, 16 * WM, nullptr}, st);
-    pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, full, rem, splits, BM, 16 * WM, ws}, st);
+        pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, full, 1, BM, 16 * WM, nullptr}, false, st);
+    const PipeRange R{n_mt, n_nt, full, rem, splits, BM, 16 * WM, ws};
+    const bool defer_sum = pending && epi == EPI_RESID;  // the caller adds the slices up (launch_resid_norm_rows)
+    pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, defer_sum, st);
+    if (defer_sum) *pending = R;
     return true;
 }
 
 template <int BDT>
 static void gemm_rows(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                       const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, bool pipe_ok,
-                      int wm, hipStream_t st) {
+                      int wm, PipeRange *pending, hipStream_t st) {
     if (pipe_ok) {
-        const bool done = wm == 1   ? pipe_plan<BDT, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st)
-                          : wm == 2 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st)
-                                    : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, st);
+        const bool done = wm == 1   ? pipe_plan<BDT, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, st)
+                          : wm == 2 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, st)
+                                    : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, st);
         if (done) return;
     }
     // largest tile that still gives every one of the 256 CUs two workgroups
@@ -1211,7 +1279,8 @@ static void gemm_rows(int epi, const uint16_t *Ahi, const uint16_t *Alo, const u
 
 template <int BDT>
 static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
-                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, hipStream_t st) {
+                    const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, PipeRange *pending,
+                    hipStream_t st) {
     const size_t w_rows = epi == EPI_SWIGLU ? 2 * (size_t)N : (size_t)N;
     const bool fits32 = std::max((size_t)T, w_rows) * (size_t)K * 2 < ((size_t)1 << 32);  // 32-bit byte offsets
     const bool pipe_ok = K % PK == 0 && fits32 && gemm_pipe_enabled();
@@ -1222,14 +1291,25 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
     const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
     const bool rows128 = T < 1024 && ((T - 1) % 256 < 128 || ((T + 255) / 256) * n_nt < std::min(device_cu_count(), 256));
     // blocks of at most 64 rows: the 64-row tiles, whose k-loop streams the weights
-    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, T <= 64 ? 1 : (rows128 ? 2 : 4), st);
+    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, T <= 64 ? 1 : (rows128 ? 2 : 4), pending, st);
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
                  int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
-                 hipStream_t st) {
-    if (D.wdt == DT_BF16) gemm_dt<DT_BF16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, st);
-    else gemm_dt<DT_F16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, st);
+                 PipeRange *pending, hipStream_t st) {
+    if (pending) *pending = PipeRange{0, 0, 0, 0, 1, 0, 0, nullptr};  // nothing left to add unless a split launch says so
+    if (D.wdt == DT_BF16) gemm_dt<DT_BF16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, pending, st);
+    else gemm_dt<DT_F16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, pending, st);
+}
+
+void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pending, const uint16_t *gain,
+                            uint16_t *Ahi, uint16_t *Alo, hipStream_t st) {
+    if (pending.k_splits <= 1 && !gain) return;  // neither a sum nor a normalisation to do
+    const dim3 block(T <= 64 ? 1024 : 256);
+    if (D.wdt == DT_BF16)
+        hipLaunchKernelGGL(k_resid_norm_rows<DT_BF16>, dim3(T), block, 0, st, X, pending, gain, Ahi, Alo, D.H, D.eps);
+    else
+        hipLaunchKernelGGL(k_resid_norm_rows<DT_F16>, dim3(T), block, 0, st, X, pending, gain, Ahi, Alo, D.H, D.eps);
 }
 
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
