@@ -77,6 +77,31 @@ __device__ __forceinline__ gptr16 as_global16(const void *p) {
 __device__ __forceinline__ u32x4 ld_stream16(const void *p) { return __builtin_nontemporal_load(as_global16(p)); }
 __device__ __forceinline__ u32x4 ld16(const void *p) { return *as_global16(p); }
 
+// ---- two-term f16 operands of the prefill-side MFMAs ---------------------------------------------
+// split an fp32 value into two f16 terms: hi = f16(v), lo = f16(v - hi)
+__device__ __forceinline__ void split_f16(float v, uint16_t &hi, uint16_t &lo) {
+    hi = down1<DT_F16>(v);
+    lo = down1<DT_F16>(v - up1<DT_F16>(hi));
+}
+struct HiLo {
+    uint32_t hi, lo;
+};
+// two values -> packed hi pair and packed lo pair (first value in the low half)
+__device__ __forceinline__ HiLo split2_f16(float a, float b) {
+    uint16_t ah, al, bh, bl;
+    split_f16(a, ah, al);
+    split_f16(b, bh, bl);
+    return HiLo{(uint32_t)ah | ((uint32_t)bh << 16), (uint32_t)al | ((uint32_t)bl << 16)};
+}
+
+// ---- publishing data to other workgroups ---------------------------------------------------------
+// Every lane waits until its own vector-memory operations have completed; for agent-scope atomic stores that
+// means the values are at the device-coherent level.  Followed by a workgroup barrier and an arrival counter
+// increment, this is the release half of a hand-over to another workgroup.  (A workgroup-scope release fence
+// does not do this: outside threadgroup-split mode the compiler emits no wait for it at all, and the counter
+// increment could overtake another wave's stores.)
+__device__ __forceinline__ void wait_own_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // ---- wave / block reductions -------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

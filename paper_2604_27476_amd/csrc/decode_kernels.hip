@@ -266,7 +266,8 @@ template <int KDT, int D, int GQ>
 __global__ void __launch_bounds__(256)
 k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
               const int *__restrict__ d_pos, float *__restrict__ part, uint32_t *__restrict__ counters,
-              float *__restrict__ o, int max_seq, int S, float scale, WarmJob warm) {
+              float *__restrict__ o, uint16_t *__restrict__ ohi, uint16_t *__restrict__ olo, int max_seq, int S,
+              float scale, WarmJob warm) {
     constexpr int LPR = D / 8;       // lanes per row
     constexpr int RW = WAVE / LPR;   // rows per wave per load
     constexpr int UR = 4;            // loads in flight per lane (K and V each)
@@ -282,7 +283,9 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
     const int zq = blockIdx.z;
     const int n_keys = d_pos[0] + 1 + zq;
     q += (size_t)zq * gridDim.y * GQ * D;
-    o += (size_t)zq * gridDim.y * GQ * D;
+    if (o) o += (size_t)zq * gridDim.y * GQ * D;
+    if (ohi) ohi += (size_t)zq * gridDim.y * GQ * D;
+    if (olo) olo += (size_t)zq * gridDim.y * GQ * D;
     part += (size_t)zq * gridDim.y * GQ * S * (D + 4);
     counters += zq * gridDim.y;
     int chunk = (n_keys + S - 1) / S;
@@ -440,7 +443,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
         __hip_atomic_store(rec + 4 + i, at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // every thread waits for its own stores, then one thread takes an arrival ticket
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    wait_own_stores();
     __syncthreads();
     if (threadIdx.x == 0)
         ticket_s = __hip_atomic_fetch_add(&counters[kvh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -473,8 +476,14 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
             at.x += r.x * c; at.y += r.y * c; at.z += r.z * c; at.w += r.w * c;
         }
         const float inv = 1.0f / lt;
-        float4 *dst = reinterpret_cast<float4 *>(o + (size_t)(kvh * GQ + h) * D + i);
-        *dst = float4{at.x * inv, at.y * inv, at.z * inv, at.w * inv};
+        const size_t at_o = (size_t)(kvh * GQ + h) * D + i;
+        if (ohi) {  // the O projection that follows is an MFMA GEMM: its operand as f16 terms
+            const HiLo s0 = split2_f16(at.x * inv, at.y * inv), s1 = split2_f16(at.z * inv, at.w * inv);
+            *reinterpret_cast<u32x2 *>(ohi + at_o) = u32x2{s0.hi, s1.hi};
+            if (olo) *reinterpret_cast<u32x2 *>(olo + at_o) = u32x2{s0.lo, s1.lo};
+        } else {
+            *reinterpret_cast<float4 *>(o + at_o) = float4{at.x * inv, at.y * inv, at.z * inv, at.w * inv};
+        }
     }
     if (threadIdx.x == 0) __hip_atomic_store(&counters[kvh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -602,14 +611,14 @@ void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st) {
 
 template <int KDT, int DD>
 static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
-                          const int *d_pos, float *part, uint32_t *counters, float *o, const WarmJob &warm,
-                          int n_queries, hipStream_t st) {
-    const dim3 grid(G.attn_splits, D.nkv, n_queries), block(256);
+                          const int *d_pos, float *part, uint32_t *counters, float *o, uint16_t *ohi, uint16_t *olo,
+                          const WarmJob &warm, int n_queries, int n_slices, hipStream_t st) {
+    const dim3 grid(n_slices, D.nkv, n_queries), block(256);
     const float scale = 1.0f / sqrtf((float)D.d);
 #define ATTN_CASE(GQ)                                                                                          \
     case GQ:                                                                                                   \
         hipLaunchKernelGGL((k_attn_decode<KDT, DD, GQ>), grid, block, 0, st, q, kc, vc, d_pos, part, counters, o, \
-                           D.max_seq, G.attn_splits, scale, warm);                                             \
+                           ohi, olo, D.max_seq, G.attn_splits, scale, warm);                                   \
         break;
     switch (D.g()) {
         ATTN_CASE(1) ATTN_CASE(2) ATTN_CASE(3) ATTN_CASE(4) ATTN_CASE(5) ATTN_CASE(6) ATTN_CASE(7) ATTN_CASE(8)
@@ -619,8 +628,21 @@ static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uin
 }
 
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
-                        const int *d_pos, float *part, uint32_t *counters, float *o, const uint16_t *warm_w,
-                        int n_queries, hipStream_t st) {
+                        const int *d_pos, float *part, uint32_t *counters, float *o, uint16_t *ohi, uint16_t *olo,
+                        const uint16_t *warm_w, int n_queries, int host_ctx, hipStream_t st) {
+    // Context slices to launch.  A captured step cannot know the context length, so it launches all of them and
+    // the ones beyond the context return at once (or warm W_o); a caller that knows the length (host_ctx > 0:
+    // keys 0 .. host_ctx - 1 for the last query) launches only the slices some query uses, by the kernel's own rule.
+    int n_slices = G.attn_splits;
+    if (host_ctx > 0) {
+        n_slices = 1;
+        for (int z = 0; z < n_queries; ++z) {
+            const int n_keys = host_ctx - (n_queries - 1 - z);
+            int chunk = (n_keys + G.attn_splits - 1) / G.attn_splits;
+            if (chunk < ATTN_CHUNK_MIN) chunk = ATTN_CHUNK_MIN;
+            n_slices = std::max(n_slices, (n_keys + chunk - 1) / chunk);
+        }
+    }
     WarmJob warm = {nullptr, 0, 0, 0};
     static const bool warm_on = !(getenv("EDGEFM_WARM") && getenv("EDGEFM_WARM")[0] == '0');
     // worthwhile only where the matrix fits the L2s (4 MB per XCD) with room to spare, and the slices map to XCDs
@@ -632,11 +654,11 @@ void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint1
         warm.n_wg = g.blocks;
     }
     if (D.kvdt == DT_BF16) {
-        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
-        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
+        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
     } else {
-        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
-        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, warm, n_queries, st);
+        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
     }
 }
 

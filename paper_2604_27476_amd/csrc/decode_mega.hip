@@ -47,11 +47,10 @@ struct MegaSync {
 };
 
 // Grid barrier in two halves, so that loads which do not depend on other workgroups (the next stage's weights)
-// can be issued between them: the release fence of the arrival then waits for this stage's stores only, not
-// for those loads.
+// can be issued between them: the arrival then waits for this stage's stores only, not for those loads.
 // arrive: this workgroup's agent-scope stores are complete and counted.
 __device__ __forceinline__ void grid_arrive(MegaSync &sy) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // each thread waits for its own stores
+    wait_own_stores();
     __syncthreads();
     if (threadIdx.x == 0) __hip_atomic_fetch_add(sy.ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -294,7 +293,7 @@ __device__ __forceinline__ void mega_attention(const MegaArgs &a, int layer, int
         }
         astore(rec + 2 + i, at);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    wait_own_stores();
     __syncthreads();
     if (tid == 0) *ticket_s = __hip_atomic_fetch_add(&a.counters[kvh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();

@@ -40,9 +40,14 @@ void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, co
 // warm_w: W_o of this layer (workgroups without a context slice pull it into L2 for launch_gemv_resid) or null.
 // n_queries > 1: query m (q, o at + m n_q d; part and counters at + m times their single-query size) is at
 // position pos + m and sees keys 0 .. pos + m.
+// host_ctx > 0: the caller knows that the last query sees keys 0 .. host_ctx - 1 (it must agree with the device
+// counter), and only the context slices in use are launched; 0: all slices, the unused ones return at once.
+// ohi non-null: the output goes out as f16 terms ohi + olo (olo null: the rounded term alone) instead of o, the
+// A operand of an MFMA O projection.
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kcache_l,
                         const uint16_t *vcache_l, const int *d_pos, float *part, uint32_t *counters, float *o,
-                        const uint16_t *warm_w, int n_queries, hipStream_t st);
+                        uint16_t *ohi, uint16_t *olo, const uint16_t *warm_w, int n_queries, int host_ctx,
+                        hipStream_t st);
 // x <- x + W vec   (O projection: vec = o, K = n_q d;  down projection: vec = h, K = I)
 void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, const float *vec, float *x,
                        hipStream_t st);
@@ -147,9 +152,10 @@ void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Al
 // sum alone; A_lo null: the rounded term alone).  X is [T, D.H].
 void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pending, const uint16_t *gain,
                             uint16_t *Ahi, uint16_t *Alo, hipStream_t st);
-// RoPE + cache write for positions p0..p0+T-1; Qs[0][t] + Qs[1][t] = RoPE(q_t)
+// RoPE + cache write for positions p0..p0+T-1; Qs[0][t] + Qs[1][t] = RoPE(q_t), or, with Qf non-null,
+// Qf[t] = RoPE(q_t) in fp32 (the query layout of launch_attn_decode) and Qs is not written
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
-                    uint16_t *Qs, size_t q_stride, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);
+                    uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);
 // f16 attention operands of one layer for context rows j < ctx (zero up to ctx_pad, a multiple of 64):
 // Kf[kvh][j][i] <- K[l][kvh][j][i];  Vt[kvh][i][.] <- V[l][kvh][j][i], keys permuted within groups of 16
 void launch_prep_kv(const Dims &D, const uint16_t *kcache_l, const uint16_t *vcache_l, int ctx, int ctx_pad,

@@ -42,6 +42,10 @@ struct Layout {
 constexpr int ATTN_SPLITS = 64;
 constexpr int MAX_PARTIALS = 4096;
 constexpr uint32_t VERIFY_MAX = 32;  // positions per verify step (sizes its logits buffers)
+// Blocks up to this length run their attention on the decode kernel, one grid layer per position (measured at
+// context 1024, 7B shape: faster than the flash kernel up to 16 positions, slower at 32).
+constexpr int SHORT_ATTN_MAX = 16;
+static_assert(SHORT_ATTN_MAX >= MULTI_MAX, "the multi-position decode kernels share the attention scratch");
 static_assert(VERIFY_MAX * 32 <= MAX_PARTIALS, "row-argmax partials share the lm_head partial buffers");
 
 struct Sizes {
@@ -107,8 +111,8 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.q = take(qd * 4);
     L.o = take(qd * 4);
     L.h = take(I * 4);
-    L.part = take((size_t)MULTI_MAX * c->n_q_heads * ATTN_SPLITS * (d + 4) * 4);
-    L.counters = take((size_t)MULTI_MAX * c->n_kv_heads * 4);
+    L.part = take((size_t)SHORT_ATTN_MAX * c->n_q_heads * ATTN_SPLITS * (d + 4) * 4);
+    L.counters = take((size_t)SHORT_ATTN_MAX * c->n_kv_heads * 4);
     L.logits = take(V * 4);
     L.hidden = take(H * 4);
     L.part_val = take(MAX_PARTIALS * 4);
@@ -135,7 +139,7 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.subset = take(V * 4);
     L.flash_part = take(FLASH_PART_RECORDS * 128 * (d + 2) * 4);
     L.mx = take(MULTI_MAX * H * 4);
-    L.mq = take(MULTI_MAX * qd * 4);
+    L.mq = take(SHORT_ATTN_MAX * qd * 4);  // fp32 queries of a short block (both verify routes, short prefills)
     L.mo = take(MULTI_MAX * qd * 4);
     L.mh = take(MULTI_MAX * I * 4);
     L.mhidden = take(MULTI_MAX * H * 4);
@@ -174,6 +178,7 @@ struct edgefm_model {
     int n_part;        // lm_head partial count
     uint32_t n_subset; // candidate tokens of a pruned vocabulary (0 = the whole vocabulary)
     int act_terms;     // f16 terms per GEMM input activation on the prefill path: 2 (hi + lo) or 1 (rounded)
+    bool short_attn;   // blocks of up to SHORT_ATTN_MAX positions use the decode attention
     bool multi_ok;     // the multi-position decode kernels may be used for short verify blocks
     bool verify_was_gemv;  // which buffers hold the last verify step's hidden states
     std::vector<LayerW> LW;
@@ -212,7 +217,7 @@ void enqueue_decode(edgefm_model *m, hipStream_t st) {
         launch_qkv(D, m->G, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
                    m->vc(l), st);
         launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                           m->at<uint32_t>(m->L.counters), o, W.wo, 1, st);
+                           m->at<uint32_t>(m->L.counters), o, nullptr, nullptr, W.wo, 1, 0, st);
         launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st);
         launch_gateup(D, m->G, W, x, h, st);
         launch_gemv_resid(D, m->G, W.w_down, D.I, h, x, st);
@@ -251,7 +256,7 @@ void enqueue_verify_gemv(edgefm_model *m, int T, hipStream_t st) {
         launch_qkv_m(D, m->G, T, W, x, m->at<float>(m->L.rope_cos), m->at<float>(m->L.rope_sin), m->d_pos(), q, m->kc(l),
                      m->vc(l), st);
         launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                           m->at<uint32_t>(m->L.counters), o, nullptr, T, st);
+                           m->at<uint32_t>(m->L.counters), o, nullptr, nullptr, nullptr, T, 0, st);
         launch_gemv_resid_m(D, m->G, T, W.wo, D.qd(), o, x, st);
         launch_gateup_m(D, m->G, T, W, x, h, st);
         launch_gemv_resid_m(D, m->G, T, W.w_down, D.I, h, x, st);
@@ -402,6 +407,9 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
         const char *vm = getenv("EDGEFM_VERIFY");
         m->multi_ok = !(vm && vm[0] == 'g') && multi_prepare() == hipSuccess;
         m->verify_was_gemv = false;
+        // EDGEFM_SHORT_ATTN=flash keeps short blocks on the flash-attention kernel as well
+        const char *sa = getenv("EDGEFM_SHORT_ATTN");
+        m->short_attn = !(sa && sa[0] == 'f');
     }
     {
         // The fused single-launch step is correct but, as measured, slower than the graph of per-stage kernels
@@ -494,7 +502,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     }
     launch_fill_u16(m->at<uint16_t>(m->L.sync), 32, 0, m->stream);
     // attention arrival counters and the step parameters start at zero (fill kernel, not a memset node)
-    launch_fill_u16(m->at<uint16_t>(m->L.counters), (size_t)MULTI_MAX * D.nkv * 2, 0, m->stream);
+    launch_fill_u16(m->at<uint16_t>(m->L.counters), (size_t)SHORT_ATTN_MAX * D.nkv * 2, 0, m->stream);
     launch_fill_u16(m->at<uint16_t>(m->L.ints), 32, 0, m->stream);
     LOADCHK(hipStreamSynchronize(m->stream));
     LOADCHK(hipGetLastError());
@@ -554,15 +562,25 @@ int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
                       (int)n_tokens, X, st);
     // The sums of the split O and down GEMMs run fused with the normalisation that follows each of them.
     PipeRange pend;
+    const bool short_block = T <= SHORT_ATTN_MAX && m->short_attn;
+    float *qf = m->at<float>(m->L.mq);
     launch_rmsnorm_rows(D, X, m->LW[0].attn_norm, T, Ahi, Alo, st);
     for (int l = 0; l < D.L; ++l) {
         const LayerW &W = m->LW[l];
         const edgefm_model::PrefillW &P = m->PW[l];
         launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, D.qkv_bias ? W.bqkv : nullptr, QKV, nullptr,
                     nullptr, ws, nullptr, st);
-        launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, m->kc(l), m->vc(l), st);
-        launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
-        launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, m->at<float>(m->L.flash_part), st);
+        if (short_block) {
+            // few queries against a long context: the decode attention, one grid layer per position (the device
+            // position counter still reads p0 here), its output written as the O GEMM's f16 operand
+            launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, qf, m->kc(l), m->vc(l), st);
+            launch_attn_decode(D, m->G, qf, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
+                               m->at<uint32_t>(m->L.counters), nullptr, Ohi, Olo, nullptr, T, ctx, st);
+        } else {
+            launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, nullptr, m->kc(l), m->vc(l), st);
+            launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
+            launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, m->at<float>(m->L.flash_part), st);
+        }
         launch_gemm(D, EPI_RESID, Ohi, Olo, P.wo, T, D.H, D.qd(), nullptr, X, nullptr, nullptr, ws, &pend, st);
         if (l == D.L - 1 && last_row_only) {
             // Nothing reads the last layer's MLP output except the final norm of the last position (the
@@ -852,7 +870,7 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat) 
                 break;
             case EDGEFM_OP_ATTN:
                 launch_attn_decode(D, m->G, q, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
-                                   m->at<uint32_t>(m->L.counters), o, W.wo, 1, st);
+                                   m->at<uint32_t>(m->L.counters), o, nullptr, nullptr, W.wo, 1, 0, st);
                 break;
             case EDGEFM_OP_OPROJ: launch_gemv_resid(D, m->G, W.wo, D.qd(), o, x, st); break;
             case EDGEFM_OP_GATEUP: launch_gateup(D, m->G, W, x, h, st); break;

@@ -50,22 +50,6 @@ __global__ void k_embed_rows(const uint16_t *__restrict__ E, const uint16_t *__r
     }
 }
 
-// split an fp32 value into two f16 terms: hi = f16(v), lo = f16(v - hi)
-__device__ __forceinline__ void split_f16(float v, uint16_t &hi, uint16_t &lo) {
-    hi = down1<DT_F16>(v);
-    lo = down1<DT_F16>(v - up1<DT_F16>(hi));
-}
-struct HiLo {
-    uint32_t hi, lo;
-};
-// two values -> packed hi pair and packed lo pair (first value in the low half)
-__device__ __forceinline__ HiLo split2_f16(float a, float b) {
-    uint16_t ah, al, bh, bl;
-    split_f16(a, ah, al);
-    split_f16(b, bh, bl);
-    return HiLo{(uint32_t)ah | ((uint32_t)bh << 16), (uint32_t)al | ((uint32_t)bl << 16)};
-}
-
 // A_hi[t] + A_lo[t] = RMSNorm(X[t]) * gain  (f16 pair; Alo may be null: only the rounded term is kept)
 template <int DT>
 __global__ void k_rmsnorm_rows(const float *__restrict__ X, const uint16_t *__restrict__ gain,
@@ -713,7 +697,8 @@ k_resid_norm_rows(float *__restrict__ X, PipeRange R, const uint16_t *__restrict
 template <int KDT>
 __global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const float *__restrict__ rope_cos,
                           const float *__restrict__ rope_sin, uint16_t *__restrict__ Qs, size_t q_stride,
-                          uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, int nq, int nkv, int d, int max_seq) {
+                          float *__restrict__ Qf, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, int nq, int nkv,
+                          int d, int max_seq) {
     const int half = d >> 1, per_t = (nq + 2 * nkv) * half;
     const size_t total = (size_t)T * per_t;
     const int R = (nq + 2 * nkv) * d;
@@ -729,7 +714,11 @@ __global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const fl
             v0 = y0;
             v1 = y1;
         }
-        if (hh < nq) {
+        if (hh < nq && Qf) {
+            float *dst = Qf + (size_t)t * nq * d + hh * d;
+            dst[i] = v0;
+            dst[i + half] = v1;
+        } else if (hh < nq) {
             uint16_t h0, l0, h1, l1;
             split_f16(v0, h0, l0);
             split_f16(v1, h1, l1);
@@ -1313,16 +1302,16 @@ void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pen
 }
 
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
-                    uint16_t *Qs, size_t q_stride, uint16_t *kc, uint16_t *vc, hipStream_t st) {
+                    uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kc, uint16_t *vc, hipStream_t st) {
     const size_t total = (size_t)T * (D.nq + 2 * D.nkv) * (D.d / 2);
     size_t blocks = (total + 255) / 256;
     if (blocks > 65535) blocks = 65535;
     if (D.kvdt == DT_BF16)
         hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, T, p0, rope_cos, rope_sin,
-                           Qs, q_stride, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
+                           Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
     else
         hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, T, p0, rope_cos, rope_sin,
-                           Qs, q_stride, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
+                           Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
 }
 
 void launch_prep_kv(const Dims &D, const uint16_t *kc, const uint16_t *vc, int ctx, int ctx_pad, uint16_t *Kf,

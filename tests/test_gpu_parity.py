@@ -547,6 +547,41 @@ def test_short_verify_step_replays_equal_the_eager_sequence(monkeypatch):
     eager.close()
 
 
+def test_short_block_attention_routes_agree(monkeypatch):
+    """Blocks of at most 16 positions on the GEMM route take the decode attention (one grid layer per position);
+    EDGEFM_SHORT_ATTN=flash at load time keeps them on the flash-attention kernel.  Both against the oracle and
+    against each other, for verify blocks over a context and for a short prompt from an empty context."""
+    shape = TINY_BF16.with_(max_seq_len=200)
+    P = Pair(shape)
+    monkeypatch.setenv("EDGEFM_SHORT_ATTN", "flash")
+    flash = binding.Model(binding.make_config(shape, max_seq_len=200), P.w)
+    monkeypatch.delenv("EDGEFM_SHORT_ATTN")
+    rng = np.random.default_rng(23)
+    prompt = synth.make_prompt(shape, 70)
+    P.prefill(prompt)
+    flash.prefill(prompt, want_logits=False)
+    for m in (5, 8, 16, 17, 13):
+        block = rng.integers(0, shape.vocab, size=m).astype(np.int32)
+        o = P.om.forward(block, logits="all")
+        na, la = P.gm.verify_step(block, want_logits=True)
+        nb, lb = flash.verify_step(block, want_logits=True)
+        for i in range(m):
+            assert rel_l2(la[i], o["logits"][i]) <= REL_TOL and rel_l2(lb[i], o["logits"][i]) <= REL_TOL, f"m={m} row {i}"
+            assert rel_l2(la[i], lb[i]) <= 2e-4
+            check_token(int(na[i]), o["logits"][i], f"decode-attention route m={m} row {i}")
+            check_token(int(nb[i]), o["logits"][i], f"flash route m={m} row {i}")
+    P.check_kv([0, 1], [69, 70, 74, 128])
+    for T in (1, 16, 17):                                # short prompts from an empty context
+        P.om.kv_reset(0); P.gm.kv_reset(0); flash.kv_reset(0)
+        pr = synth.make_prompt(shape, T, seed=77 + T)
+        P.prefill(pr, where=f"short prompt T={T}")
+        nb, lb = flash.prefill(pr)
+        o = P.om                                          # the oracle already holds this prompt
+        assert flash.kv_len == o.kv_len == T
+    flash.close()
+    P.close()
+
+
 def test_verify_step_7b_width_context_1000():
     """The verify step at the 7B-shaped width (two layers) on top of a 1000-position context."""
     shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
