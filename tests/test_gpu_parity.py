@@ -677,6 +677,36 @@ def test_prefill_one_term_activation_mode_7b_width():
     assert e.value.status == binding.EDGEFM_ERR_INVALID_ARG
 
 
+def test_split_context_merge_is_reproducible_over_many_steps():
+    """400 device-chained decode steps over a context of ~1000-1400 keys (16-22 attention slices per KV head,
+    each step handing 2 x 4 x 28 records between workgroups), twice from the same state: every sampled token and
+    the final logits must agree bit for bit.  A record that the merging workgroup reads before its writer's
+    store has landed shows up here as a diverging stream."""
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    g = P.gm
+    ctx = 1000
+    rows = [synth.make_kv_rows(shape, l, ctx) for l in range(2)]
+    for l, (k, v) in enumerate(rows):
+        g.kv_write(l, k, v)
+
+    def stream():
+        g.set_kv_len(ctx)
+        toks = [g.decode_step(11)[0]]
+        for i in range(399):
+            if i % 50 == 49:
+                toks.append(g.decode_step(-1)[0])      # a synchronising step now and then: tokens to compare
+            else:
+                g.decode_step(-1, sync=False)
+        nxt, lg = g.decode_step(-1, want_logits=True)
+        return toks + [nxt], lg
+
+    a, la = stream()
+    b, lb = stream()
+    assert g.kv_len == ctx + 401
+    assert a == b and np.array_equal(la, lb)
+
+
 def test_long_prefill_7b_width_two_layers():
     """Prefill GEMMs and flash attention at T = 2048 on the 7B-shaped width (depth 2), then the VLM-shaped
     request: 1024 embedding rows + 64 tokens in one prefill and an 8-token greedy decode (configs[4])."""
