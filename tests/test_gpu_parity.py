@@ -180,6 +180,15 @@ def test_embedding_rows_then_tokens():
     emb = synth.make_visual_embeds(shape, 70)
     P.run(synth.make_prompt(shape, 20), 5, embeds=emb)
     assert P.gm.kv_len == 95
+    # embedding rows alone (no token follows them), then tokens appended to them in a second prefill
+    P.om.kv_reset(0); P.gm.kv_reset(0)
+    P.prefill(None, emb[:33], where="embedding rows only")
+    assert P.gm.kv_len == 33
+    P.prefill(synth.make_prompt(shape, 9, seed=3), where="tokens after the embedding rows")
+    P.check_kv([0, 1], [0, 32, 33, 41])
+    with pytest.raises(binding.EdgefmError) as e:        # an empty prefill is an error and changes nothing
+        P.gm.prefill(None, None)
+    assert e.value.status == binding.EDGEFM_ERR_INVALID_ARG and P.gm.kv_len == 42
     P.close()
 
 
