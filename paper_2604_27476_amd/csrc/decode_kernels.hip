@@ -26,7 +26,7 @@ __global__ void k_embed(const uint16_t *__restrict__ E, const int *__restrict__ 
 // y_i = x_i cos - x_{i+d/2} sin, y_{i+d/2} = x_{i+d/2} cos + x_i sin (slice / negate / concat form of
 // Appendix B.3).  V heads use the same pairing without rotation.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int KDT>
+template <int DT, int KDT, int NV>
 __global__ void __launch_bounds__(1024)
 k_qkv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const uint16_t *__restrict__ gain,
       const float *__restrict__ x, const float *__restrict__ rope_cos, const float *__restrict__ rope_sin,
@@ -37,13 +37,22 @@ k_qkv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const u
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int half = d >> 1, n_units = (nq + 2 * nkv) * half, nvec = H >> 3;
     const int unit0 = blockIdx.x * nw + wave;
-    Chunk<2, 7> pre;
-    if (unit0 < n_units) {  // weights first: they do not depend on the activations
-        const int hh = unit0 / half, r0 = hh * d + (unit0 - hh * half);
+    Chunk<2, 7> pre;  // the first weights are requested before the vector is staged: they do not depend on it
+    if constexpr (NV > 0) {
+        VecRegs<NV, true> xr;
+        vec_fetch<DT, NV, true>(xr, x, gain, H);
+        const int u0 = min(unit0, n_units - 1), hh = u0 / half, r0 = hh * d + (u0 - hh * half);
         const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)(r0 + half) * H};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit<DT, NV, true>(xr, H, eps, smem, red);
+    } else {
+        if (unit0 < n_units) {
+            const int hh = unit0 / half, r0 = hh * d + (unit0 - hh * half);
+            const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)(r0 + half) * H};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
+        stage_vec<DT, true>(x, gain, H, eps, smem, red);
     }
-    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     const int pos = d_pos[0];
     for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int hh = unit / half, i = unit - hh * half;
@@ -82,8 +91,10 @@ k_qkv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const u
 // ------------------------------------------------------------------------------------------------
 // x[r] += W[r] . vec  (O projection and down projection with the residual add in the epilogue)
 // ------------------------------------------------------------------------------------------------
-template <int DT>
-__global__ void __launch_bounds__(1024)
+// NV: groups of eight vector values per thread fetched ahead of the weight prefetch (0: staged afterwards; 6 is
+// for workgroups of at most eight waves, which have the registers for it).
+template <int DT, int NV>
+__global__ void __launch_bounds__(NV > 1 ? 512 : 1024)
 k_gemv_resid(const uint16_t *__restrict__ W, const float *__restrict__ vec, float *__restrict__ x, int rows_n,
              int K) {
     extern __shared__ float4 smem[];
@@ -92,11 +103,20 @@ k_gemv_resid(const uint16_t *__restrict__ W, const float *__restrict__ vec, floa
     const int n_units = (rows_n + 1) >> 1, nvec = K >> 3;
     const int unit0 = blockIdx.x * nw + wave;
     Chunk<2, 7> pre;
-    if (unit0 < n_units) {
-        const uint16_t *rows[2] = {W + (size_t)(2 * unit0) * K, W + (size_t)min(2 * unit0 + 1, rows_n - 1) * K};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
+    if constexpr (NV > 0) {
+        VecRegs<NV, false> xr;
+        vec_fetch<DT, NV, false>(xr, vec, nullptr, K);
+        const int u0 = min(unit0, n_units - 1);
+        const uint16_t *rows[2] = {W + (size_t)(2 * u0) * K, W + (size_t)min(2 * u0 + 1, rows_n - 1) * K};
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit<DT, NV, false>(xr, K, 0.f, smem, red);
+    } else {
+        if (unit0 < n_units) {
+            const uint16_t *rows[2] = {W + (size_t)(2 * unit0) * K, W + (size_t)min(2 * unit0 + 1, rows_n - 1) * K};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
+        stage_vec<DT, false>(vec, nullptr, K, 0.f, smem, red);
     }
-    stage_vec<DT, false>(vec, nullptr, K, 0.f, smem, red);
     for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int r0 = 2 * unit, r1 = min(2 * unit + 1, rows_n - 1);
         const uint16_t *rows[2] = {W + (size_t)r0 * K, W + (size_t)r1 * K};
@@ -112,7 +132,7 @@ k_gemv_resid(const uint16_t *__restrict__ W, const float *__restrict__ vec, floa
 // ------------------------------------------------------------------------------------------------
 // gate/up GEMV with RMSNorm prologue and SwiGLU epilogue: unit j = rows (j, I + j)
 // ------------------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, int NV>
 __global__ void __launch_bounds__(1024)
 k_gateup(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
          float *__restrict__ h, int H, int I, float eps) {
@@ -122,11 +142,20 @@ k_gateup(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
     const int nvec = H >> 3;
     const int j0 = blockIdx.x * nw + wave;
     Chunk<2, 7> pre;
-    if (j0 < I) {
-        const uint16_t *rows[2] = {W + (size_t)j0 * H, W + (size_t)(I + j0) * H};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
+    if constexpr (NV > 0) {
+        VecRegs<NV, true> xr;
+        vec_fetch<DT, NV, true>(xr, x, gain, H);
+        const int jc = min(j0, I - 1);
+        const uint16_t *rows[2] = {W + (size_t)jc * H, W + (size_t)(I + jc) * H};
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit<DT, NV, true>(xr, H, eps, smem, red);
+    } else {
+        if (j0 < I) {
+            const uint16_t *rows[2] = {W + (size_t)j0 * H, W + (size_t)(I + j0) * H};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
+        stage_vec<DT, true>(x, gain, H, eps, smem, red);
     }
-    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     for (int j = j0; j < I; j += gridDim.x * nw) {
         const uint16_t *rows[2] = {W + (size_t)j * H, W + (size_t)(I + j) * H};
         float o[2];
@@ -139,7 +168,7 @@ k_gateup(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
 // lm_head GEMV with final-RMSNorm prologue; logits are stored and each block keeps its (max, lowest
 // index) so that greedy sampling needs no second pass over the logits.
 // ------------------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, int NV>
 __global__ void __launch_bounds__(1024)
 k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
          float *__restrict__ logits, float *__restrict__ hidden, float *__restrict__ part_val,
@@ -156,11 +185,20 @@ k_lmhead(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, cons
     const int unit0 = blockIdx.x * nw + wave;
     auto token_of = [&](int i) { return subset ? subset[i] : i; };
     Chunk<2, 7> pre;
-    if (unit0 < n_units) {
-        const uint16_t *rows[2] = {W + (size_t)token_of(2 * unit0) * H, W + (size_t)token_of(min(2 * unit0 + 1, V - 1)) * H};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
+    if constexpr (NV > 0) {
+        VecRegs<NV, true> xr;
+        vec_fetch<DT, NV, true>(xr, x, gain, H);
+        const int u0 = min(unit0, n_units - 1);
+        const uint16_t *rows[2] = {W + (size_t)token_of(2 * u0) * H, W + (size_t)token_of(min(2 * u0 + 1, V - 1)) * H};
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit<DT, NV, true>(xr, H, eps, smem, red);
+    } else {
+        if (unit0 < n_units) {
+            const uint16_t *rows[2] = {W + (size_t)token_of(2 * unit0) * H, W + (size_t)token_of(min(2 * unit0 + 1, V - 1)) * H};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
+        stage_vec<DT, true>(x, gain, H, eps, smem, red);
     }
-    stage_vec<DT, true>(x, gain, H, eps, smem, red);
     if (blockIdx.x == 0) {  // export the final hidden state (the tensor the parity tolerance is stated on)
         for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
             reinterpret_cast<float4 *>(hidden)[2 * v] = smem[v];
@@ -527,18 +565,36 @@ hipError_t kernels_prepare(const Dims &D) {
 #define PREP(K)                                                                                              \
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, n); \
     if (e != hipSuccess) return e;
-    PREP(k_gemv_resid<DT_BF16>)
-    PREP(k_gemv_resid<DT_F16>)
-    PREP(k_gateup<DT_BF16>)
-    PREP(k_gateup<DT_F16>)
-    PREP(k_lmhead<DT_BF16>)
-    PREP(k_lmhead<DT_F16>)
-    PREP((k_qkv<DT_BF16, DT_BF16>))
-    PREP((k_qkv<DT_BF16, DT_F16>))
-    PREP((k_qkv<DT_F16, DT_BF16>))
-    PREP((k_qkv<DT_F16, DT_F16>))
+    PREP((k_gemv_resid<DT_BF16, 0>))
+    PREP((k_gemv_resid<DT_F16, 0>))
+    PREP((k_gemv_resid<DT_BF16, 1>))
+    PREP((k_gemv_resid<DT_F16, 1>))
+    PREP((k_gemv_resid<DT_BF16, 6>))
+    PREP((k_gemv_resid<DT_F16, 6>))
+    PREP((k_gateup<DT_BF16, 0>))
+    PREP((k_gateup<DT_F16, 0>))
+    PREP((k_gateup<DT_BF16, 1>))
+    PREP((k_gateup<DT_F16, 1>))
+    PREP((k_lmhead<DT_BF16, 0>))
+    PREP((k_lmhead<DT_F16, 0>))
+    PREP((k_lmhead<DT_BF16, 1>))
+    PREP((k_lmhead<DT_F16, 1>))
+    PREP((k_qkv<DT_BF16, DT_BF16, 0>))
+    PREP((k_qkv<DT_BF16, DT_F16, 0>))
+    PREP((k_qkv<DT_F16, DT_BF16, 0>))
+    PREP((k_qkv<DT_F16, DT_F16, 0>))
+    PREP((k_qkv<DT_BF16, DT_BF16, 1>))
+    PREP((k_qkv<DT_BF16, DT_F16, 1>))
+    PREP((k_qkv<DT_F16, DT_BF16, 1>))
+    PREP((k_qkv<DT_F16, DT_F16, 1>))
 #undef PREP
     return hipSuccess;
+}
+
+// EDGEFM_EARLY_FETCH=0: stage the activation vector after the weight prefetch (the older order), for comparison
+static bool early_fetch() {
+    static const bool on = !(getenv("EDGEFM_EARLY_FETCH") && getenv("EDGEFM_EARLY_FETCH")[0] == '0');
+    return on;
 }
 
 void launch_embed(const Dims &D, const uint16_t *embed, const int *d_token, float *x, hipStream_t st) {
@@ -551,28 +607,44 @@ void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, co
     const size_t lds = (size_t)D.H * 4;
     const GemvGrid g = gemv_grid(D.R() / 2, G.n_cu, lds);
     const uint16_t *bias = D.qkv_bias ? W.bqkv : nullptr;
-#define QKV_LAUNCH(WDT, KDT)                                                                                     \
-    hipLaunchKernelGGL((k_qkv<WDT, KDT>), dim3(g.blocks), dim3(g.threads), lds, st, W.wqkv, bias, W.attn_norm, x, \
+    const bool early = early_fetch() && D.H / 8 <= g.threads;
+#define QKV_LAUNCH1(WDT, KDT, NV)                                                                                    \
+    hipLaunchKernelGGL((k_qkv<WDT, KDT, NV>), dim3(g.blocks), dim3(g.threads), lds, st, W.wqkv, bias, W.attn_norm, x, \
                        rope_cos, rope_sin, d_pos, q, kc, vc, D.H, D.nq, D.nkv, D.d, D.max_seq, D.eps)
+#define QKV_LAUNCH(WDT, KDT)               \
+    do {                                   \
+        if (early) QKV_LAUNCH1(WDT, KDT, 1); \
+        else QKV_LAUNCH1(WDT, KDT, 0);     \
+    } while (0)
     if (D.wdt == DT_BF16 && D.kvdt == DT_BF16) QKV_LAUNCH(DT_BF16, DT_BF16);
     else if (D.wdt == DT_BF16) QKV_LAUNCH(DT_BF16, DT_F16);
     else if (D.kvdt == DT_BF16) QKV_LAUNCH(DT_F16, DT_BF16);
     else QKV_LAUNCH(DT_F16, DT_F16);
 #undef QKV_LAUNCH
+#undef QKV_LAUNCH1
 }
 
 void launch_gemv_resid(const Dims &D, const Geo &G, const uint16_t *W, int K, const float *vec, float *x,
                        hipStream_t st) {
     const size_t lds = (size_t)K * 4;
     const GemvGrid g = gemv_grid((D.H + 1) / 2, G.n_cu, lds);
-    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_gemv_resid<DT>, dim3(g.blocks), dim3(g.threads), lds, st, W, vec, x, D.H, K);)
+    // vector loads ahead of the weight prefetch where a thread's share of the vector fits its registers
+    const int nvec = K / 8, nv = !early_fetch() ? 0 : nvec <= g.threads ? 1 : (g.threads <= 512 && nvec <= 6 * g.threads) ? 6 : 0;
+    if (nv == 1) { DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_gemv_resid<DT, 1>), dim3(g.blocks), dim3(g.threads), lds, st, W, vec, x, D.H, K);) }
+    else if (nv == 6) { DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_gemv_resid<DT, 6>), dim3(g.blocks), dim3(g.threads), lds, st, W, vec, x, D.H, K);) }
+    else { DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_gemv_resid<DT, 0>), dim3(g.blocks), dim3(g.threads), lds, st, W, vec, x, D.H, K);) }
 }
 
 void launch_gateup(const Dims &D, const Geo &G, const LayerW &W, const float *x, float *h, hipStream_t st) {
     const size_t lds = (size_t)D.H * 4;
     const GemvGrid g = gemv_grid(D.I, G.n_cu, lds);
-    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_gateup<DT>, dim3(g.blocks), dim3(g.threads), lds, st, W.w_gate_up,
-                                        W.mlp_norm, x, h, D.H, D.I, D.eps);)
+    if (early_fetch() && D.H / 8 <= g.threads) {
+        DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_gateup<DT, 1>), dim3(g.blocks), dim3(g.threads), lds, st, W.w_gate_up,
+                                            W.mlp_norm, x, h, D.H, D.I, D.eps);)
+    } else {
+        DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_gateup<DT, 0>), dim3(g.blocks), dim3(g.threads), lds, st, W.w_gate_up,
+                                            W.mlp_norm, x, h, D.H, D.I, D.eps);)
+    }
 }
 
 int lmhead_blocks(const Dims &D, const Geo &G) {
@@ -586,8 +658,13 @@ void launch_lmhead(const Dims &D, const Geo &G, const uint16_t *lm, const uint16
     const int n_rows = subset ? n_subset : D.V;
     const GemvGrid g = gemv_grid((n_rows + 1) / 2, G.n_cu, lds);
     *n_part = g.blocks;
-    DT_SWITCH(D.wdt, hipLaunchKernelGGL(k_lmhead<DT>, dim3(g.blocks), dim3(g.threads), lds, st, lm, final_norm, x,
-                                        logits, hidden, part_val, part_idx, D.H, n_rows, D.eps, subset);)
+    if (early_fetch() && D.H / 8 <= g.threads) {
+        DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_lmhead<DT, 1>), dim3(g.blocks), dim3(g.threads), lds, st, lm, final_norm, x,
+                                            logits, hidden, part_val, part_idx, D.H, n_rows, D.eps, subset);)
+    } else {
+        DT_SWITCH(D.wdt, hipLaunchKernelGGL((k_lmhead<DT, 0>), dim3(g.blocks), dim3(g.threads), lds, st, lm, final_norm, x,
+                                            logits, hidden, part_val, part_idx, D.H, n_rows, D.eps, subset);)
+    }
 }
 
 void launch_finish(const float *part_val, const int *part_idx, int n_part, int *d_next, int *d_token, int *d_pos,

@@ -100,6 +100,76 @@ __device__ __forceinline__ void stage_vec(const float *__restrict__ x, const uin
 }
 
 // ------------------------------------------------------------------------------------------------
+// The same staging in two steps, for kernels that prefetch weights before they stage the vector.  Vector-memory
+// results return to a wave in issue order, so a lane that waits for loads issued after the prefetch also waits
+// for the prefetch, and the weight latency ends up in front of the staging instead of behind it.  vec_fetch
+// issues the loads of this thread's share (up to NV groups of eight values, and their gains) BEFORE the weight
+// prefetch; vec_commit, called after the prefetch has been issued, waits for those loads only, reduces,
+// normalises and writes the LDS layout of stage_vec.  Indices are clamped instead of branched around, so that
+// the compiler counts the loads in flight exactly.  Requires n / 8 <= NV * blockDim.x.
+// ------------------------------------------------------------------------------------------------
+template <int NV, bool NORM> struct VecRegs {
+    float4 a[NV], b[NV];
+    u32x4 g[NORM ? NV : 1];
+};
+template <int DT, int NV, bool NORM>
+__device__ __forceinline__ void vec_fetch(VecRegs<NV, NORM> &r, const float *__restrict__ x,
+                                          const uint16_t *__restrict__ gain, int n) {
+    const int nvec = n >> 3;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int v = min((int)(threadIdx.x + j * blockDim.x), nvec - 1);
+        r.a[j] = reinterpret_cast<const float4 *>(x)[2 * v];
+        r.b[j] = reinterpret_cast<const float4 *>(x)[2 * v + 1];
+        if constexpr (NORM) r.g[j] = ld16(gain + 8 * v);
+    }
+}
+template <int DT, int NV, bool NORM>
+__device__ __forceinline__ void vec_commit(const VecRegs<NV, NORM> &r, int n, float eps, float4 *xs, float *red) {
+    const int nvec = n >> 3;
+    float rstd = 1.f;
+    if constexpr (NORM) {
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            if ((int)(threadIdx.x + j * blockDim.x) < nvec) {
+                const float4 a = r.a[j], b = r.b[j];
+                ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+            }
+        }
+        ss = block_sum(ss, red);
+        rstd = 1.0f / sqrtf(ss / (float)n + eps);
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int v = threadIdx.x + j * blockDim.x;
+        if (v < nvec) {
+            float4 a = r.a[j], b = r.b[j];
+            if constexpr (NORM) {
+                float g[8];
+                unpack8<DT>(r.g[j], g);
+                a.x = a.x * rstd * g[0]; a.y = a.y * rstd * g[1]; a.z = a.z * rstd * g[2]; a.w = a.w * rstd * g[3];
+                b.x = b.x * rstd * g[4]; b.y = b.y * rstd * g[5]; b.z = b.z * rstd * g[6]; b.w = b.w * rstd * g[7];
+            }
+            xs[v] = a;
+            xs[nvec + v] = b;
+        }
+    }
+    __syncthreads();
+}
+// The first chunk of a wave's rows, unconditionally (vector index clamped into the row; chunk_fma never uses
+// the slots beyond nvec): no branch between these loads and the waits that follow.
+template <int NR, int U>
+__device__ __forceinline__ void chunk_load_clamped(Chunk<NR, U> &c, const uint16_t *const (&rows)[NR], int v0, int nvec) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int v = min(v0 + u * WAVE, nvec - 1);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) c.w[u][r] = ld_stream16(rows[r] + (size_t)v * 8);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // The same against M staged vectors at once (vector m at xs + 2 nvec m): every weight vector is loaded and
 // unpacked once and used for all M dot products.  The verify step of speculative decoding streams the
 // weights once for M positions this way.
