@@ -34,13 +34,24 @@ k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const
     const int half = d >> 1, n_units = (nq + 2 * nkv) * half, nvec = H >> 3, qd = nq * d;
     const int unit0 = blockIdx.x * nw + wave;
     Chunk<2, 7> pre;
-    if (unit0 < n_units) {  // weights first: they do not depend on the activations
-        const int hh = unit0 / half, r0 = hh * d + (unit0 - hh * half);
+    if (nvec <= (int)blockDim.x) {
+        // the M vectors are requested before the first weights (which do not depend on them) and staged from
+        // registers: vector-memory results return in issue order, so loads behind the prefetch would wait for it
+        VecRegsM<M> xr;
+        vec_fetch_m<DT, M>(xr, x, (size_t)H, gain, H);
+        const int u0 = min(unit0, n_units - 1), hh = u0 / half, r0 = hh * d + (u0 - hh * half);
         const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)(r0 + half) * H};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
-    }
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit_m<DT, M>(xr, H, eps, smem, red);
+    } else {
+        if (unit0 < n_units) {
+            const int hh = unit0 / half, r0 = hh * d + (unit0 - hh * half);
+            const uint16_t *rows[2] = {W + (size_t)r0 * H, W + (size_t)(r0 + half) * H};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
 #pragma unroll 1
-    for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+        for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+    }
     const int pos = d_pos[0];
     for (int unit = unit0; unit < n_units; unit += gridDim.x * nw) {
         const int hh = unit / half, i = unit - hh * half;
@@ -131,12 +142,21 @@ k_gateup_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, co
     const int nvec = H >> 3;
     const int j0 = blockIdx.x * nw + wave;
     Chunk<2, 7> pre;
-    if (j0 < I) {
-        const uint16_t *rows[2] = {W + (size_t)j0 * H, W + (size_t)(I + j0) * H};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
-    }
+    if (nvec <= (int)blockDim.x) {  // vectors first, then the weights, then the staging (see k_qkv_m)
+        VecRegsM<M> xr;
+        vec_fetch_m<DT, M>(xr, x, (size_t)H, gain, H);
+        const int jc = min(j0, I - 1);
+        const uint16_t *rows[2] = {W + (size_t)jc * H, W + (size_t)(I + jc) * H};
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit_m<DT, M>(xr, H, eps, smem, red);
+    } else {
+        if (j0 < I) {
+            const uint16_t *rows[2] = {W + (size_t)j0 * H, W + (size_t)(I + j0) * H};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
 #pragma unroll 1
-    for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+        for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+    }
     for (int j = j0; j < I; j += gridDim.x * nw) {
         const uint16_t *rows[2] = {W + (size_t)j * H, W + (size_t)(I + j) * H};
         float acc[M][2];
@@ -166,12 +186,21 @@ k_lmhead_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, co
     const int unit0 = blockIdx.x * nw + wave;
     auto token_of = [&](int i) { return subset ? subset[i] : i; };
     Chunk<2, 7> pre;
-    if (unit0 < n_units) {
-        const uint16_t *rows[2] = {W + (size_t)token_of(2 * unit0) * H, W + (size_t)token_of(min(2 * unit0 + 1, n_rows - 1)) * H};
-        chunk_load<2, 7>(pre, rows, lane, nvec);
-    }
+    if (nvec <= (int)blockDim.x) {  // vectors first, then the weights, then the staging (see k_qkv_m)
+        VecRegsM<M> xr;
+        vec_fetch_m<DT, M>(xr, x, (size_t)H, gain, H);
+        const int u0 = min(unit0, n_units - 1);
+        const uint16_t *rows[2] = {W + (size_t)token_of(2 * u0) * H, W + (size_t)token_of(min(2 * u0 + 1, n_rows - 1)) * H};
+        chunk_load_clamped<2, 7>(pre, rows, lane, nvec);
+        vec_commit_m<DT, M>(xr, H, eps, smem, red);
+    } else {
+        if (unit0 < n_units) {
+            const uint16_t *rows[2] = {W + (size_t)token_of(2 * unit0) * H, W + (size_t)token_of(min(2 * unit0 + 1, n_rows - 1)) * H};
+            chunk_load<2, 7>(pre, rows, lane, nvec);
+        }
 #pragma unroll 1
-    for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+        for (int m = 0; m < M; ++m) stage_vec<DT, true>(x + (size_t)m * H, gain, H, eps, smem + 2 * nvec * m, red);
+    }
     if (blockIdx.x == 0) {  // export the final hidden states (the tensors the parity tolerance is stated on)
         for (int m = 0; m < M; ++m)
             for (int v = threadIdx.x; v < nvec; v += blockDim.x) {

@@ -157,6 +157,43 @@ __device__ __forceinline__ void vec_commit(const VecRegs<NV, NORM> &r, int n, fl
     }
     __syncthreads();
 }
+// The same for M vectors of n values each (vector m at x + m * stride), normalised with one gain and staged at
+// xs + 2 (n / 8) m.  Requires n / 8 <= blockDim.x.
+template <int M> struct VecRegsM {
+    float4 a[M], b[M];
+    u32x4 g;
+};
+template <int DT, int M>
+__device__ __forceinline__ void vec_fetch_m(VecRegsM<M> &r, const float *__restrict__ x, size_t stride,
+                                            const uint16_t *__restrict__ gain, int n) {
+    const int v = min((int)threadIdx.x, (n >> 3) - 1);
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        r.a[m] = reinterpret_cast<const float4 *>(x + m * stride)[2 * v];
+        r.b[m] = reinterpret_cast<const float4 *>(x + m * stride)[2 * v + 1];
+    }
+    r.g = ld16(gain + 8 * v);
+}
+template <int DT, int M>
+__device__ __forceinline__ void vec_commit_m(const VecRegsM<M> &r, int n, float eps, float4 *xs, float *red) {
+    const int nvec = n >> 3, v = threadIdx.x;
+    float g[8];
+    unpack8<DT>(r.g, g);
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        float4 a = r.a[m], b = r.b[m];
+        float ss = v < nvec ? a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w : 0.f;
+        ss = block_sum(ss, red);
+        const float rstd = 1.0f / sqrtf(ss / (float)n + eps);
+        if (v < nvec) {
+            a.x = a.x * rstd * g[0]; a.y = a.y * rstd * g[1]; a.z = a.z * rstd * g[2]; a.w = a.w * rstd * g[3];
+            b.x = b.x * rstd * g[4]; b.y = b.y * rstd * g[5]; b.z = b.z * rstd * g[6]; b.w = b.w * rstd * g[7];
+            xs[2 * nvec * m + v] = a;
+            xs[2 * nvec * m + nvec + v] = b;
+        }
+    }
+    __syncthreads();
+}
 // The first chunk of a wave's rows, unconditionally (vector index clamped into the row; chunk_fma never uses
 // the slots beyond nvec): no branch between these loads and the waits that follow.
 template <int NR, int U>
