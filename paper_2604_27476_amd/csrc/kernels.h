@@ -143,8 +143,9 @@ struct PipeRange {
     int wn_out;  // SwiGLU outputs per wave tile: the tile's columns are wn_out gate rows, wn_out up rows, ...
     float *ws;
 };
-// pending (EPI_RESID only, may be null): the sum of the k-slices of split tiles is left to the caller, who
-// passes *pending to launch_resid_norm_rows before ws is used again; k_splits == 1 there means nothing is left.
+// pending (EPI_RESID and EPI_BIAS_F32, may be null): the sum of the k-slices of split tiles (and for EPI_BIAS_F32
+// the bias of those tiles) is left to the caller, who passes *pending to launch_resid_norm_rows (EPI_RESID) or
+// launch_rope_kv (the QKV GEMM) before ws is used again; k_splits == 1 there means nothing is left.
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
                  int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
                  PipeRange *pending, hipStream_t st);
@@ -154,8 +155,11 @@ void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pen
                             uint16_t *Ahi, uint16_t *Alo, hipStream_t st);
 // RoPE + cache write for positions p0..p0+T-1; Qs[0][t] + Qs[1][t] = RoPE(q_t), or, with Qf non-null,
 // Qf[t] = RoPE(q_t) in fp32 (the query layout of launch_attn_decode) and Qs is not written
+// pending, bias: what the QKV GEMM left to add (see launch_gemm); the elements of split tiles are then taken
+// from the k-slices, not from QKV
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
-                    uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kcache_l, uint16_t *vcache_l, hipStream_t st);
+                    uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kcache_l, uint16_t *vcache_l,
+                    const PipeRange &pending, const uint16_t *bias, hipStream_t st);
 // f16 attention operands of one layer for context rows j < ctx (zero up to ctx_pad, a multiple of 64):
 // Kf[kvh][j][i] <- K[l][kvh][j][i];  Vt[kvh][i][.] <- V[l][kvh][j][i], keys permuted within groups of 16
 void launch_prep_kv(const Dims &D, const uint16_t *kcache_l, const uint16_t *vcache_l, int ctx, int ctx_pad,

@@ -568,16 +568,17 @@ int enqueue_layers(edgefm_model *m, const int32_t *tok_host, uint32_t n_tokens, 
     for (int l = 0; l < D.L; ++l) {
         const LayerW &W = m->LW[l];
         const edgefm_model::PrefillW &P = m->PW[l];
-        launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, D.qkv_bias ? W.bqkv : nullptr, QKV, nullptr,
-                    nullptr, ws, nullptr, st);
+        const uint16_t *bqkv = D.qkv_bias ? W.bqkv : nullptr;
+        PipeRange pend_qkv;  // the slice sums of the QKV GEMM (and their bias) are taken by the RoPE kernel
+        launch_gemm(D, EPI_BIAS_F32, Ahi, Alo, P.wqkv, T, D.R(), D.H, bqkv, QKV, nullptr, nullptr, ws, &pend_qkv, st);
         if (short_block) {
             // few queries against a long context: the decode attention, one grid layer per position (the device
             // position counter still reads p0 here), its output written as the O GEMM's f16 operand
-            launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, qf, m->kc(l), m->vc(l), st);
+            launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, qf, m->kc(l), m->vc(l), pend_qkv, bqkv, st);
             launch_attn_decode(D, m->G, qf, m->kc(l), m->vc(l), m->d_pos(), m->at<float>(m->L.part),
                                m->at<uint32_t>(m->L.counters), nullptr, Ohi, Olo, nullptr, T, ctx, st);
         } else {
-            launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, nullptr, m->kc(l), m->vc(l), st);
+            launch_rope_kv(D, QKV, T, p0, rc, rs, Qs, q_stride, nullptr, m->kc(l), m->vc(l), pend_qkv, bqkv, st);
             launch_prep_kv(D, m->kc(l), m->vc(l), ctx, ctx_pad, Kf, Vt, st);
             launch_flash_attn(D, Qs, q_stride, Kf, Vt, ctx_pad, T, p0, Ohi, Olo, m->at<float>(m->L.flash_part), st);
         }

@@ -694,19 +694,37 @@ k_resid_norm_rows(float *__restrict__ X, PipeRange R, const uint16_t *__restrict
 // One thread per (t, head, i < d/2).  The rotated query is stored as two f16 terms (q = q_hi + q_lo, term s
 // at Qs + s * q_stride): the MFMA partner of the f16 copy of K that k_prep_kv makes.
 // ------------------------------------------------------------------------------------------------
+// If the QKV GEMM left the k-slices of its split tiles pending (P.k_splits > 1), the value of such an element is
+// their sum in slice order plus the bias; elements of tiles that were not split are in QKV already.
 template <int KDT>
-__global__ void k_rope_kv(const float *__restrict__ QKV, int T, int p0, const float *__restrict__ rope_cos,
+__global__ void k_rope_kv(const float *__restrict__ QKV, PipeRange P, const uint16_t *__restrict__ bias, int bias_dt,
+                          int T, int p0, const float *__restrict__ rope_cos,
                           const float *__restrict__ rope_sin, uint16_t *__restrict__ Qs, size_t q_stride,
                           float *__restrict__ Qf, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, int nq, int nkv,
                           int d, int max_seq) {
     const int half = d >> 1, per_t = (nq + 2 * nkv) * half;
     const size_t total = (size_t)T * per_t;
     const int R = (nq + 2 * nkv) * d;
+    const size_t slice = (size_t)P.n_tiles * (P.bm * P_BN);
+    auto value = [&](int t, int col) -> float {
+        if (P.k_splits > 1) {
+            const int mt = t / P.bm, r = t - mt * P.bm, nb = col / P_BN, o = col - nb * P_BN;
+            const int gid = mt / GROUP_M, first_m = gid * GROUP_M, gm = min(GROUP_M, P.n_mt - first_m);
+            const int tl = gid * GROUP_M * P.n_nt + nb * gm + (mt - first_m) - P.tile_begin;  // see pipe_tile
+            if (tl >= 0 && tl < P.n_tiles) {
+                const float *wt = P.ws + (size_t)tl * (P.bm * P_BN) + r * P_BN + o;
+                float s = 0.f;
+                for (int sl = 0; sl < P.k_splits; ++sl) s += wt[sl * slice];
+                if (bias) s += bias_dt == DT_BF16 ? up1<DT_BF16>(bias[col]) : up1<DT_F16>(bias[col]);
+                return s;
+            }
+        }
+        return QKV[(size_t)t * R + col];
+    };
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
         const int t = (int)(idx / per_t), u = (int)(idx - (size_t)t * per_t);
         const int hh = u / half, i = u - hh * half;
-        const float *row = QKV + (size_t)t * R + hh * d;
-        float v0 = row[i], v1 = row[i + half];
+        float v0 = value(t, hh * d + i), v1 = value(t, hh * d + i + half);
         const int pos = p0 + t;
         if (hh < nq + nkv) {
             const float c = rope_cos[(size_t)pos * half + i], s = rope_sin[(size_t)pos * half + i];
@@ -1240,7 +1258,8 @@ static bool pipe_plan(int epi, const uint16_t *Ahi, const uint16_t *Alo, const u
     if (full > 0)
         pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, full, 1, BM, 16 * WM, nullptr}, false, st);
     const PipeRange R{n_mt, n_nt, full, rem, splits, BM, 16 * WM, ws};
-    const bool defer_sum = pending && epi == EPI_RESID;  // the caller adds the slices up (launch_resid_norm_rows)
+    // the caller adds the slices up (launch_resid_norm_rows; launch_rope_kv for the QKV GEMM)
+    const bool defer_sum = pending && (epi == EPI_RESID || epi == EPI_BIAS_F32);
     pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, defer_sum, st);
     if (defer_sum) *pending = R;
     return true;
@@ -1302,15 +1321,16 @@ void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pen
 }
 
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
-                    uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kc, uint16_t *vc, hipStream_t st) {
+                    uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kc, uint16_t *vc, const PipeRange &pending,
+                    const uint16_t *bias, hipStream_t st) {
     const size_t total = (size_t)T * (D.nq + 2 * D.nkv) * (D.d / 2);
     size_t blocks = (total + 255) / 256;
     if (blocks > 65535) blocks = 65535;
     if (D.kvdt == DT_BF16)
-        hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, T, p0, rope_cos, rope_sin,
+        hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
                            Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
     else
-        hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, T, p0, rope_cos, rope_sin,
+        hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
                            Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
 }
 
