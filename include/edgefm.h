@@ -198,6 +198,13 @@ typedef enum {
 } edgefm_op;
 int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat);
 
+/* Host arithmetic only (no device call, no model): how the prefill side cuts a GEMM of T rows, N outputs and
+ * depth K on n_cu compute units into tiles, full rounds and k-slices.  `swiglu` != 0: N counts neurons, the
+ * weight has 2 N rows (gate | up).  out_host[8] = {tile rows, row tiles, column tiles, tiles, tiles in full
+ * rounds, tiles of the last round, k-slices of those, 1 if the pipelined kernel takes the GEMM}.
+ * Errors: INVALID_ARG (NULL, a zero size, n_cu not in 1..256). */
+int edgefm_debug_gemm_plan(uint32_t T, uint32_t N, uint32_t K, int swiglu, uint32_t n_cu, int32_t *out_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -149,6 +149,10 @@ struct PipeRange {
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
                  int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
                  PipeRange *pending, hipStream_t st);
+// The cut of a GEMM as launch_gemm would make it on n_cu compute units (host arithmetic, no device call):
+// out = {tile rows, row tiles, column tiles, tiles, tiles in full rounds, tiles of the last round, k-slices of
+// those, 1 if the pipelined kernel takes the GEMM}
+void debug_gemm_plan(int epi, int T, int N, int K, int n_cu, int out[8]);
 // X[t] += the k-slices a residual GEMM left pending;  A_hi[t] + A_lo[t] <- RMSNorm(X[t]) * gain  (gain null: the
 // sum alone; A_lo null: the rounded term alone).  X is [T, D.H].
 void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pending, const uint16_t *gain,

@@ -743,6 +743,15 @@ int edgefm_set_prefill_precision(edgefm_model *m, int mode) {
     return EDGEFM_OK;
 }
 
+int edgefm_debug_gemm_plan(uint32_t T, uint32_t N, uint32_t K, int swiglu, uint32_t n_cu, int32_t *out_host) {
+    if (!out_host || !T || !N || !K || n_cu < 1 || n_cu > 256 || T > (1u << 20) || N > (1u << 30) || K > (1u << 30))
+        return EDGEFM_ERR_INVALID_ARG;
+    int out[8];
+    debug_gemm_plan(swiglu ? EPI_SWIGLU : EPI_RESID, (int)T, (int)N, (int)K, (int)n_cu, out);
+    for (int i = 0; i < 8; ++i) out_host[i] = out[i];
+    return EDGEFM_OK;
+}
+
 uint32_t edgefm_kv_len(const edgefm_model *m) { return m ? m->kv_len : 0; }
 
 int edgefm_last_hip_error(const edgefm_model *m) { return m ? m->last_hip : 0; }

@@ -1229,29 +1229,51 @@ static void pipe_launch(int epi, const uint16_t *Ahi, const uint16_t *Alo, const
     else pipe_launch_terms<BDT, WM, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R, defer_sum, st);
 }
 
-// Full rounds of tiles (one per CU) in one launch; the tiles of a partly filled last round are cut along K
-// instead, so that the round is short and busy on every CU, and their slices meet in the workspace.
+// How a [T, N] x K GEMM is cut (host arithmetic only).  Tile rows: 256, or 128 where 256-row tiles would be at
+// least half empty in their last row of tiles (they cost about a tenth more per row, so long prompts stay with
+// 256) or, for prompts below 1024, would not even give every CU one tile, or 64 for blocks of at most 64 rows
+// (their k-loop streams the weights).  Mixing two shapes in one GEMM measured slower: neither launch fills the
+// machine.  Full rounds of tiles (one per CU) go out in one launch; the tiles of a partly filled last round are
+// cut along K instead, so that the round is short and busy on every CU, and their slices meet in the workspace:
+// the slice count is the one that minimises rounds x (k-tiles per unit + overhead), within the workspace.  With
+// about a round's worth of tiles or less this is the largest count that still fits one round; with the 148
+// gate/up column tiles of a 64-row block it is three (two short rounds).
+struct GemmPlan {
+    int wm, bm, n_mt, n_nt, tiles, full, rem, splits;
+    bool pipe;  // false: fewer than half of the CUs would get a tile and nothing can be cut: the tile kernels' job
+};
+static GemmPlan gemm_plan(int epi, int T, int N, int K, int n_cu, bool have_ws) {
+    GemmPlan p;
+    const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
+    const bool rows128 = T < 1024 && ((T - 1) % 256 < 128 || ((T + 255) / 256) * n_nt < n_cu);
+    p.wm = T <= 64 ? 1 : (rows128 ? 2 : 4);
+    p.bm = 64 * p.wm;
+    p.n_mt = (T + p.bm - 1) / p.bm;
+    p.n_nt = n_nt;
+    p.tiles = p.n_mt * p.n_nt;
+    p.rem = p.tiles % n_cu;
+    p.full = p.tiles - p.rem;
+    p.splits = 1;
+    const int nk = K / PK;
+    if (p.rem > 0 && have_ws) {
+        const int kmax = std::min(p.wm == 1 ? 2 * PIPE_MAX_SPLITS : PIPE_MAX_SPLITS,
+                                  nk / (p.wm == 1 ? PIPE_MIN_SLICE_TILES / 2 : PIPE_MIN_SLICE_TILES));
+        auto cost = [&](int k) { return (float)((p.rem * k + n_cu - 1) / n_cu) * ((float)nk / (float)k + PIPE_UNIT_OVERHEAD); };
+        for (int k = 2; k <= kmax; ++k)
+            if ((size_t)p.rem * k * p.bm * P_BN * 4 <= GEMM_WS_BYTES && cost(k) < 0.97f * cost(p.splits)) p.splits = k;
+    }
+    p.pipe = p.splits >= 2 || p.tiles * 2 >= n_cu;
+    return p;
+}
+
 template <int BDT, int WM>
 static bool pipe_plan(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                       const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, PipeRange *pending,
-                      hipStream_t st) {
+                      const GemmPlan &p, hipStream_t st) {
     constexpr int BM = 64 * WM;
-    const int n_mt = (T + BM - 1) / BM;
-    const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
-    const int n_cu = std::min(device_cu_count(), 256), tiles = n_mt * n_nt, nk = K / PK;
-    const int rem = tiles % n_cu, full = tiles - rem;
-    // k-slices for the tiles of the last round: the count that minimises rounds x (k-tiles per unit + overhead),
-    // within the workspace.  With about a round's worth of tiles or less this is the largest count that still
-    // fits one round; with the 148 gate/up column tiles of a 64-row block it is three (two short rounds).
-    int splits = 1;
-    if (rem > 0 && ws) {
-        const int kmax = std::min(WM == 1 ? 2 * PIPE_MAX_SPLITS : PIPE_MAX_SPLITS, nk / (WM == 1 ? PIPE_MIN_SLICE_TILES / 2 : PIPE_MIN_SLICE_TILES));
-        auto cost = [&](int k) { return (float)((rem * k + n_cu - 1) / n_cu) * ((float)nk / (float)k + PIPE_UNIT_OVERHEAD); };
-        for (int k = 2; k <= kmax; ++k)
-            if ((size_t)rem * k * BM * P_BN * 4 <= GEMM_WS_BYTES && cost(k) < 0.97f * cost(splits)) splits = k;
-    }
+    const int n_mt = p.n_mt, n_nt = p.n_nt, tiles = p.tiles, full = p.full, rem = p.rem, splits = p.splits;
+    if (!p.pipe) return false;
     if (splits < 2) {
-        if (tiles * 2 < n_cu) return false;  // fewer than half of the CUs would work: leave it to the tile kernels
         pipe_launch<BDT, WM>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, PipeRange{n_mt, n_nt, 0, tiles, 1, BM, 16 * WM, nullptr}, false, st);
         return true;
     }
@@ -1268,11 +1290,12 @@ static bool pipe_plan(int epi, const uint16_t *Ahi, const uint16_t *Alo, const u
 template <int BDT>
 static void gemm_rows(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W, int T, int N, int K,
                       const uint16_t *bias, float *outf, uint16_t *ohi, uint16_t *olo, float *ws, bool pipe_ok,
-                      int wm, PipeRange *pending, hipStream_t st) {
+                      PipeRange *pending, hipStream_t st) {
     if (pipe_ok) {
-        const bool done = wm == 1   ? pipe_plan<BDT, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, st)
-                          : wm == 2 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, st)
-                                    : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, st);
+        const GemmPlan p = gemm_plan(epi, T, N, K, std::min(device_cu_count(), 256), ws != nullptr);
+        const bool done = p.wm == 1   ? pipe_plan<BDT, 1>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, p, st)
+                          : p.wm == 2 ? pipe_plan<BDT, 2>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, p, st)
+                                      : pipe_plan<BDT, 4>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pending, p, st);
         if (done) return;
     }
     // largest tile that still gives every one of the 256 CUs two workgroups
@@ -1292,14 +1315,7 @@ static void gemm_dt(int epi, const uint16_t *Ahi, const uint16_t *Alo, const uin
     const size_t w_rows = epi == EPI_SWIGLU ? 2 * (size_t)N : (size_t)N;
     const bool fits32 = std::max((size_t)T, w_rows) * (size_t)K * 2 < ((size_t)1 << 32);  // 32-bit byte offsets
     const bool pipe_ok = K % PK == 0 && fits32 && gemm_pipe_enabled();
-    // 128-row tiles where 256-row tiles would be at least half empty in their last row of tiles (they cost
-    // about a tenth more per row, so long prompts stay with 256).  Mixing the two shapes in one GEMM (256-row
-    // body, 128-row tail, separate launches) measured slower: neither launch fills the machine.
-    // ... or, for prompts below 1024, would not even give every CU one tile.
-    const int n_nt = epi == EPI_SWIGLU ? (N + P_BN / 2 - 1) / (P_BN / 2) : (N + P_BN - 1) / P_BN;
-    const bool rows128 = T < 1024 && ((T - 1) % 256 < 128 || ((T + 255) / 256) * n_nt < std::min(device_cu_count(), 256));
-    // blocks of at most 64 rows: the 64-row tiles, whose k-loop streams the weights
-    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, T <= 64 ? 1 : (rows128 ? 2 : 4), pending, st);
+    gemm_rows<BDT>(epi, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, ws, pipe_ok, pending, st);
 }
 
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
@@ -1308,6 +1324,12 @@ void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Al
     if (pending) *pending = PipeRange{0, 0, 0, 0, 1, 0, 0, nullptr};  // nothing left to add unless a split launch says so
     if (D.wdt == DT_BF16) gemm_dt<DT_BF16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, pending, st);
     else gemm_dt<DT_F16>(epi, Ahi, Alo, W16, T, N, K, bias, out_f32, out_hi, out_lo, ws, pending, st);
+}
+
+void debug_gemm_plan(int epi, int T, int N, int K, int n_cu, int out[8]) {
+    const GemmPlan p = gemm_plan(epi, T, N, K, n_cu, true);
+    out[0] = p.bm; out[1] = p.n_mt; out[2] = p.n_nt; out[3] = p.tiles; out[4] = p.full; out[5] = p.rem;
+    out[6] = p.splits; out[7] = p.pipe ? 1 : 0;
 }
 
 void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pending, const uint16_t *gain,

@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 import synth
@@ -92,3 +93,61 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "lib_path", lambda: str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="not found"):
         binding.load_library()
+
+
+def _plan(lib, T, N, K, swiglu=0, n_cu=256):
+    out = np.zeros(8, np.int32)
+    st = lib.edgefm_debug_gemm_plan(T, N, K, swiglu, n_cu, out.ctypes.data_as(C.c_void_p))
+    assert st == binding.EDGEFM_OK
+    return dict(zip(("bm", "n_mt", "n_nt", "tiles", "full", "rem", "splits", "pipe"), (int(v) for v in out)))
+
+
+def test_gemm_plan_known_cuts_of_the_7b_shape(lib):
+    """Host logic of the prefill GEMMs: the cuts of the 7B-shaped layer at the sizes the benchmark runs."""
+    H, I, R = 3584, 18944, 4608
+    p = _plan(lib, 1024, I, H, swiglu=1)                # gate/up: 592 tiles = two full rounds + 80 tiles in 3 slices
+    assert (p["bm"], p["tiles"], p["full"], p["rem"], p["splits"], p["pipe"]) == (256, 592, 512, 80, 3, 1)
+    p = _plan(lib, 1024, H, I)                          # down: 56 tiles, four slices each, one round
+    assert (p["bm"], p["tiles"], p["full"], p["rem"], p["splits"]) == (256, 56, 0, 56, 4)
+    p = _plan(lib, 1024, R, H)                          # QKV: 72 tiles x 3 slices
+    assert (p["tiles"], p["splits"]) == (72, 3)
+    p = _plan(lib, 8, I, H, swiglu=1)                   # a verify block: 148 column tiles of 64 rows in 3 slices
+    assert (p["bm"], p["n_mt"], p["tiles"], p["splits"]) == (64, 1, 148, 3)
+    p = _plan(lib, 300, I, H, swiglu=1)                 # 300 rows: 128-row tiles (a third 256-row tile would be 7/8 empty)
+    assert (p["bm"], p["n_mt"]) == (128, 3)
+    p = _plan(lib, 449, I, H, swiglu=1)                 # 449 rows fill most of two 256-row tiles
+    assert (p["bm"], p["n_mt"]) == (256, 2)
+    p = _plan(lib, 128, 64, 64)                         # one tile on 256 CUs and too shallow to cut: not for this kernel
+    assert p["pipe"] == 0
+
+
+def test_gemm_plan_invariants_over_a_grid_of_shapes(lib):
+    """Whatever the shape: the tiles cover the matrix, full rounds are whole, the last round is smaller than a
+    round, its slices respect their bounds (count, depth, workspace), and a GEMM is only refused when fewer than
+    half of the CUs would get a tile."""
+    ws_bytes = 64 << 20
+    for n_cu in (256, 64, 1):
+        for T in (1, 7, 64, 65, 128, 129, 300, 449, 512, 1023, 1024, 1025, 4096, 8192):
+            for (N, K, sw) in ((3584, 3584, 0), (4608, 3584, 0), (18944, 3584, 1), (3584, 18944, 0), (152064, 3584, 0),
+                               (896, 896, 0), (4864, 896, 1), (896, 4864, 0), (100, 96, 0), (1000, 32, 1)):
+                p = _plan(lib, T, N, K, sw, n_cu)
+                assert p["bm"] in (64, 128, 256) and (p["bm"] == 64) == (T <= 64)
+                assert p["n_mt"] == -(-T // p["bm"]) and p["n_nt"] == -(-N // (128 if sw else 256))
+                assert p["tiles"] == p["n_mt"] * p["n_nt"] == p["full"] + p["rem"]
+                assert p["full"] % n_cu == 0 and 0 <= p["rem"] < n_cu
+                k_tiles = K // 32
+                max_slices, min_depth = (16, 8) if p["bm"] == 64 else (8, 16)
+                assert 1 <= p["splits"] <= max_slices
+                if p["splits"] > 1:
+                    assert p["rem"] > 0 and k_tiles // p["splits"] >= min_depth
+                    assert p["rem"] * p["splits"] * p["bm"] * 256 * 4 <= ws_bytes
+                assert p["pipe"] == (1 if (p["splits"] > 1 or 2 * p["tiles"] >= n_cu) else 0)
+
+
+def test_gemm_plan_rejects_bad_arguments(lib):
+    out = np.zeros(8, np.int32)
+    ptr = out.ctypes.data_as(C.c_void_p)
+    assert lib.edgefm_debug_gemm_plan(0, 8, 32, 0, 256, ptr) == binding.EDGEFM_ERR_INVALID_ARG
+    assert lib.edgefm_debug_gemm_plan(8, 8, 32, 0, 0, ptr) == binding.EDGEFM_ERR_INVALID_ARG
+    assert lib.edgefm_debug_gemm_plan(8, 8, 32, 0, 257, ptr) == binding.EDGEFM_ERR_INVALID_ARG
+    assert lib.edgefm_debug_gemm_plan(8, 8, 32, 0, 256, None) == binding.EDGEFM_ERR_INVALID_ARG
