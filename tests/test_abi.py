@@ -151,3 +151,24 @@ def test_gemm_plan_rejects_bad_arguments(lib):
     assert lib.edgefm_debug_gemm_plan(8, 8, 32, 0, 0, ptr) == binding.EDGEFM_ERR_INVALID_ARG
     assert lib.edgefm_debug_gemm_plan(8, 8, 32, 0, 257, ptr) == binding.EDGEFM_ERR_INVALID_ARG
     assert lib.edgefm_debug_gemm_plan(8, 8, 32, 0, 256, None) == binding.EDGEFM_ERR_INVALID_ARG
+
+
+def test_workload_shapes_and_decode_byte_counts_match_the_fixture():
+    """tests/golden/workload_shapes.txt: the shapes of the evaluated decoders and, from the definition of the
+    decode step (every parameter once per token plus the K/V rows of the context), the bytes a step moves.  The
+    benchmark's roofline figures divide these byte counts by measured times, so the generator's accounting is
+    held to the formula evaluated here and to the stored numbers."""
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "workload_shapes.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for name, L, H, nq, nkv, d, I, V, tied, step_bytes, kv_bytes in rows:
+        L, H, nq, nkv, d, I, V, tied, step_bytes, kv_bytes = map(int, (L, H, nq, nkv, d, I, V, tied, step_bytes, kv_bytes))
+        s = synth.SHAPES[name]
+        assert (s.n_layers, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.intermediate, s.vocab) == (L, H, nq, nkv, d, I, V)
+        assert bool(s.tie_embeddings) == bool(tied) and s.qkv_bias
+        R = (nq + 2 * nkv) * d
+        per_layer = 2 * (R * H + H * nq * d + 2 * I * H + H * I) + 2 * 2 * H + 2 * R
+        step = L * per_layer + 2 * V * H + 2 * 2 * H
+        assert step == step_bytes == s.weight_bytes_per_token()
+        assert L * 2 * nkv * d * 2 == kv_bytes == s.kv_bytes_per_context_token()
+    assert synth.SHAPES["qwen2.5-7b-shaped"].weight_bytes_per_token() / 1e9 == pytest.approx(14.141, abs=1e-3)
