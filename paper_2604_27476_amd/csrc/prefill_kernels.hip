@@ -702,54 +702,68 @@ __global__ void k_rope_kv(const float *__restrict__ QKV, PipeRange P, const uint
                           const float *__restrict__ rope_sin, uint16_t *__restrict__ Qs, size_t q_stride,
                           float *__restrict__ Qf, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, int nq, int nkv,
                           int d, int max_seq) {
-    const int half = d >> 1, per_t = (nq + 2 * nkv) * half;
+    // four adjacent elements i .. i+3 of a head's first half (and their rotation partners) per thread:
+    // 16-byte loads, 8-byte stores (d / 2 is a multiple of 4)
+    const int half = d >> 1, q4 = half >> 2, per_t = (nq + 2 * nkv) * q4;
     const size_t total = (size_t)T * per_t;
     const int R = (nq + 2 * nkv) * d;
     const size_t slice = (size_t)P.n_tiles * (P.bm * P_BN);
-    auto value = [&](int t, int col) -> float {
+    auto value4 = [&](int t, int col) -> f32x4 {
         if (P.k_splits > 1) {
             const int mt = t / P.bm, r = t - mt * P.bm, nb = col / P_BN, o = col - nb * P_BN;
             const int gid = mt / GROUP_M, first_m = gid * GROUP_M, gm = min(GROUP_M, P.n_mt - first_m);
             const int tl = gid * GROUP_M * P.n_nt + nb * gm + (mt - first_m) - P.tile_begin;  // see pipe_tile
             if (tl >= 0 && tl < P.n_tiles) {
                 const float *wt = P.ws + (size_t)tl * (P.bm * P_BN) + r * P_BN + o;
-                float s = 0.f;
-                for (int sl = 0; sl < P.k_splits; ++sl) s += wt[sl * slice];
-                if (bias) s += bias_dt == DT_BF16 ? up1<DT_BF16>(bias[col]) : up1<DT_F16>(bias[col]);
+                f32x4 s = {0.f, 0.f, 0.f, 0.f};
+                int sl = 0;
+                for (; sl + 4 <= P.k_splits; sl += 4) {  // four loads in flight, added in slice order
+                    const f32x4 p0 = *reinterpret_cast<const f32x4 *>(wt + (sl + 0) * slice);
+                    const f32x4 p1 = *reinterpret_cast<const f32x4 *>(wt + (sl + 1) * slice);
+                    const f32x4 p2 = *reinterpret_cast<const f32x4 *>(wt + (sl + 2) * slice);
+                    const f32x4 p3 = *reinterpret_cast<const f32x4 *>(wt + (sl + 3) * slice);
+                    s = (((s + p0) + p1) + p2) + p3;
+                }
+                for (; sl < P.k_splits; ++sl) s += *reinterpret_cast<const f32x4 *>(wt + sl * slice);
+                if (bias) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        s[e] += bias_dt == DT_BF16 ? up1<DT_BF16>(bias[col + e]) : up1<DT_F16>(bias[col + e]);
+                }
                 return s;
             }
         }
-        return QKV[(size_t)t * R + col];
+        return *reinterpret_cast<const f32x4 *>(QKV + (size_t)t * R + col);
     };
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
         const int t = (int)(idx / per_t), u = (int)(idx - (size_t)t * per_t);
-        const int hh = u / half, i = u - hh * half;
-        float v0 = value(t, hh * d + i), v1 = value(t, hh * d + i + half);
+        const int hh = u / q4, i = (u - hh * q4) * 4;
+        f32x4 v0 = value4(t, hh * d + i), v1 = value4(t, hh * d + i + half);
         const int pos = p0 + t;
         if (hh < nq + nkv) {
-            const float c = rope_cos[(size_t)pos * half + i], s = rope_sin[(size_t)pos * half + i];
-            const float y0 = v0 * c - v1 * s, y1 = v1 * c + v0 * s;
+            const f32x4 c = *reinterpret_cast<const f32x4 *>(rope_cos + (size_t)pos * half + i);
+            const f32x4 sn = *reinterpret_cast<const f32x4 *>(rope_sin + (size_t)pos * half + i);
+            const f32x4 y0 = v0 * c - v1 * sn, y1 = v1 * c + v0 * sn;
             v0 = y0;
             v1 = y1;
         }
         if (hh < nq && Qf) {
             float *dst = Qf + (size_t)t * nq * d + hh * d;
-            dst[i] = v0;
-            dst[i + half] = v1;
+            *reinterpret_cast<f32x4 *>(dst + i) = v0;
+            *reinterpret_cast<f32x4 *>(dst + i + half) = v1;
         } else if (hh < nq) {
-            uint16_t h0, l0, h1, l1;
-            split_f16(v0, h0, l0);
-            split_f16(v1, h1, l1);
+            const HiLo a0 = split2_f16(v0[0], v0[1]), a1 = split2_f16(v0[2], v0[3]);
+            const HiLo b0 = split2_f16(v1[0], v1[1]), b1 = split2_f16(v1[2], v1[3]);
             uint16_t *dst = Qs + (size_t)t * nq * d + hh * d;
-            dst[i] = h0;
-            dst[i + half] = h1;
-            dst[q_stride + i] = l0;
-            dst[q_stride + i + half] = l1;
+            *reinterpret_cast<u32x2 *>(dst + i) = u32x2{a0.hi, a1.hi};
+            *reinterpret_cast<u32x2 *>(dst + i + half) = u32x2{b0.hi, b1.hi};
+            *reinterpret_cast<u32x2 *>(dst + q_stride + i) = u32x2{a0.lo, a1.lo};
+            *reinterpret_cast<u32x2 *>(dst + q_stride + i + half) = u32x2{b0.lo, b1.lo};
         } else {
             uint16_t *dst = hh < nq + nkv ? kc + ((size_t)(hh - nq) * max_seq + pos) * d
                                           : vc + ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
-            dst[i] = down1<KDT>(v0);
-            dst[i + half] = down1<KDT>(v1);
+            *reinterpret_cast<u32x2 *>(dst + i) = u32x2{down2<KDT>(v0[0], v0[1]), down2<KDT>(v0[2], v0[3])};
+            *reinterpret_cast<u32x2 *>(dst + i + half) = u32x2{down2<KDT>(v1[0], v1[1]), down2<KDT>(v1[2], v1[3])};
         }
     }
 }
@@ -1345,14 +1359,15 @@ void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pen
 void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float *rope_cos, const float *rope_sin,
                     uint16_t *Qs, size_t q_stride, float *Qf, uint16_t *kc, uint16_t *vc, const PipeRange &pending,
                     const uint16_t *bias, hipStream_t st) {
-    const size_t total = (size_t)T * (D.nq + 2 * D.nkv) * (D.d / 2);
-    size_t blocks = (total + 255) / 256;
+    const size_t total = (size_t)T * (D.nq + 2 * D.nkv) * (D.d / 8);  // four adjacent elements of a half per thread
+    const unsigned threads = total < 256 * 256 ? 64 : 256;  // short blocks: one wave per workgroup, on as many CUs as possible
+    size_t blocks = (total + threads - 1) / threads;
     if (blocks > 65535) blocks = 65535;
     if (D.kvdt == DT_BF16)
-        hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
+        hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(threads), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
                            Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
     else
-        hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
+        hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(threads), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
                            Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
 }
 
