@@ -205,6 +205,12 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat);
  * Errors: INVALID_ARG (NULL, a zero size, n_cu not in 1..256). */
 int edgefm_debug_gemm_plan(uint32_t T, uint32_t N, uint32_t K, int swiglu, uint32_t n_cu, int32_t *out_host);
 
+/* Test-only, process-wide: plan the cuts of the prefill GEMMs as for n_cu compute units (1..256) instead of the
+ * device's count; 0 restores.  A small n_cu makes short prompts take the cuts that otherwise need thousands of
+ * rows (full rounds of tiles followed by a k-sliced last round).  Results do not depend on it beyond summation
+ * order.  Errors: INVALID_ARG (n_cu > 256). */
+int edgefm_debug_set_gemm_plan_cus(uint32_t n_cu);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,6 +29,7 @@ EXPORTS = [
     "edgefm_debug_kv_write", "edgefm_debug_kv_fill", "edgefm_debug_set_kv_len", "edgefm_debug_last_hidden",
     "edgefm_debug_launch_op", "edgefm_debug_stage_trace", "edgefm_set_vocab_subset", "edgefm_verify_step",
     "edgefm_debug_verify_hidden", "edgefm_set_prefill_precision", "edgefm_debug_gemm_plan",
+    "edgefm_debug_set_gemm_plan_cus",
 ]
 
 
@@ -69,6 +70,7 @@ def load_library():
     lib.edgefm_kv_len.argtypes = [m]
     lib.edgefm_set_prefill_precision.argtypes = [m, C.c_int]
     lib.edgefm_debug_gemm_plan.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, C.c_uint32, C.c_void_p]
+    lib.edgefm_debug_set_gemm_plan_cus.argtypes = [C.c_uint32]
     lib.edgefm_kv_len.restype = C.c_uint32
     lib.edgefm_model_free.argtypes = [m]
     lib.edgefm_model_free.restype = None
@@ -221,6 +223,10 @@ class Model:
         out = np.empty(self.cfg.hidden, dtype=np.float32)
         _check(self.lib.edgefm_debug_verify_hidden(self.h, row, _np_ptr(out)), "edgefm_debug_verify_hidden")
         return out
+
+    def set_gemm_plan_cus(self, n_cu: int):
+        """edgefm_debug_set_gemm_plan_cus (process-wide; 0 restores the device's count)."""
+        _check(self.lib.edgefm_debug_set_gemm_plan_cus(n_cu), "edgefm_debug_set_gemm_plan_cus")
 
     def set_prefill_precision(self, mode: int):
         """edgefm_set_prefill_precision: EDGEFM_PREFILL_F16 or EDGEFM_PREFILL_F16X2."""

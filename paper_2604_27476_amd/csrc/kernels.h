@@ -153,6 +153,9 @@ void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Al
 // out = {tile rows, row tiles, column tiles, tiles, tiles in full rounds, tiles of the last round, k-slices of
 // those, 1 if the pipelined kernel takes the GEMM}
 void debug_gemm_plan(int epi, int T, int N, int K, int n_cu, int out[8]);
+// Plan the GEMM cuts of this process for n compute units instead of the device's (0 restores): tiles beyond a
+// "round" of n then take the split path although the chip has room, which is correct and only slower.
+void debug_set_gemm_plan_cus(int n);
 // X[t] += the k-slices a residual GEMM left pending;  A_hi[t] + A_lo[t] <- RMSNorm(X[t]) * gain  (gain null: the
 // sum alone; A_lo null: the rounded term alone).  X is [T, D.H].
 void launch_resid_norm_rows(const Dims &D, float *X, int T, const PipeRange &pending, const uint16_t *gain,

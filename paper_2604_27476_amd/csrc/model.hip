@@ -752,6 +752,12 @@ int edgefm_debug_gemm_plan(uint32_t T, uint32_t N, uint32_t K, int swiglu, uint3
     return EDGEFM_OK;
 }
 
+int edgefm_debug_set_gemm_plan_cus(uint32_t n_cu) {
+    if (n_cu > 256) return EDGEFM_ERR_INVALID_ARG;
+    debug_set_gemm_plan_cus((int)n_cu);
+    return EDGEFM_OK;
+}
+
 uint32_t edgefm_kv_len(const edgefm_model *m) { return m ? m->kv_len : 0; }
 
 int edgefm_last_hip_error(const edgefm_model *m) { return m ? m->last_hip : 0; }

@@ -1200,7 +1200,12 @@ static bool gemm_pipe_enabled() {
     return state == 1;
 }
 
+// Compute units the GEMM cut is planned for: the device's, unless a test has set a smaller number to reach,
+// at small sizes, the cuts that need thousands of rows on the whole chip (full rounds plus a split last round).
+static int g_plan_cus = 0;
+void debug_set_gemm_plan_cus(int n) { g_plan_cus = n > 0 && n <= 256 ? n : 0; }
 static int device_cu_count() {
+    if (g_plan_cus) return g_plan_cus;
     static int n = 0;
     if (!n) {
         int dev = 0;

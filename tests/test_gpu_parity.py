@@ -716,6 +716,31 @@ def test_split_context_merge_is_reproducible_over_many_steps():
     assert a == b and np.array_equal(la, lb)
 
 
+def test_prefill_gemms_with_full_rounds_and_a_split_last_round():
+    """On the whole chip only prompts of thousands of rows give a GEMM both full rounds of tiles (written by the
+    GEMM epilogue) and a k-sliced last round (summed by the RoPE kernel, the fused residual + RMSNorm kernel or the
+    SwiGLU sum).  Planning the cuts for 32 compute units brings that mix to prompts of a few hundred rows, where
+    the oracle can follow: QKV 32 + 22 x 4, O and down 32 + 10 x 3 at T = 300; every GEMM mixed at T = 449."""
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    try:
+        P.gm.set_gemm_plan_cus(32)
+        for T in (300, 449):
+            P.om.kv_reset(0); P.gm.kv_reset(0)
+            P.prefill(synth.make_prompt(shape, T, seed=synth.SEED_PROMPT + 7 * T), where=f"32-CU plan, T={T}")
+            P.check_kv([0, 1], [0, T - 1])
+        P.prefill(synth.make_prompt(shape, 130, seed=12), where="32-CU plan, 130 rows appended to 449")
+        tok = P.decode(3, "decode after the 32-CU plan")
+        P.gm.set_prefill_precision(binding.EDGEFM_PREFILL_F16)      # the one-term kernels take the same cuts
+        P.om.kv_reset(0); P.gm.kv_reset(0)
+        o = P.om.prefill(synth.make_prompt(shape, 300, seed=5))
+        g_next, g_logits = P.gm.prefill(synth.make_prompt(shape, 300, seed=5))
+        assert rel_l2(g_logits, o["logits"]) <= F16_MODE_TOL
+    finally:
+        P.gm.set_prefill_precision(binding.EDGEFM_PREFILL_F16X2)
+        P.gm.set_gemm_plan_cus(0)
+
+
 def test_long_prefill_7b_width_two_layers():
     """Prefill GEMMs and flash attention at T = 2048 on the 7B-shaped width (depth 2), then the VLM-shaped
     request: 1024 embedding rows + 64 tokens in one prefill and an 8-token greedy decode (configs[4])."""
