@@ -38,12 +38,13 @@ typedef ORACLE_REAL real;
 
 #define ORACLE_F16 1
 #define ORACLE_BF16 2
+#define ORACLE_FP8 3 /* e4m3, no infinities, largest finite value 448: KV-cache storage only; code in the low byte */
 
 typedef struct {
     uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab;
     uint32_t max_seq_len;
     double rms_eps, rope_theta;
-    uint32_t weight_dtype, kv_dtype;  /* ORACLE_F16 / ORACLE_BF16 */
+    uint32_t weight_dtype, kv_dtype;  /* weights: ORACLE_F16 / ORACLE_BF16; cache: those or ORACLE_FP8 */
     uint32_t tie_embeddings, qkv_bias;
     uint32_t kv_round; /* 1: cache holds values rounded to kv_dtype (the method); 0: unrounded (diagnostic) */
 } oracle_config;
@@ -72,6 +73,14 @@ static double bits_to_double(uint16_t b, uint32_t dtype) {
         memcpy(&f, &u, 4);
         return (double)f;
     }
+    if (dtype == ORACLE_FP8) { /* sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent 15 with mantissa 7 is NaN */
+        int s8 = (b >> 7) & 1, e8 = (b >> 3) & 15, m8 = b & 7;
+        double v8;
+        if (e8 == 15 && m8 == 7) v8 = NAN;
+        else if (e8 == 0) v8 = ldexp((double)m8, -9);
+        else v8 = ldexp((double)(8 + m8), e8 - 10);
+        return s8 ? -v8 : v8;
+    }
     /* IEEE binary16 */
     int sign = (b >> 15) & 1, e = (b >> 10) & 31, m = b & 1023;
     double v;
@@ -98,6 +107,10 @@ static double round_to_format(double x, int p, int emin, double maxv) {
 
 double oracle_round_kv(double x, uint32_t dtype) {
     if (dtype == ORACLE_BF16) return round_to_format(x, 8, -126, 3.3895313892515355e38);
+    if (dtype == ORACLE_FP8) { /* the format has no infinity: what rounds beyond 448 stays at 448 */
+        double r = round_to_format(x, 4, -6, 448.0);
+        return isinf(r) ? (r > 0 ? 448.0 : -448.0) : r;
+    }
     return round_to_format(x, 11, -14, 65504.0);
 }
 

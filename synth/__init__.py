@@ -28,6 +28,7 @@ import numpy as np
 
 F16 = 1
 BF16 = 2
+FP8 = 3   # 8-bit e4m3 (no infinities, one NaN code per sign, largest finite value 448): KV-cache storage only
 
 SEED_WEIGHTS = 27476
 SEED_PROMPT = 27477
@@ -119,11 +120,55 @@ def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
 
 
+def _fp8_table() -> np.ndarray:
+    """Value of each of the 256 e4m3 codes (sign, 4 exponent bits with bias 7, 3 mantissa bits; 0x7f / 0xff = NaN)."""
+    t = np.empty(256, np.float32)
+    for c in range(256):
+        e, m = (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            v = np.nan
+        elif e == 0:
+            v = m * 2.0 ** -9
+        else:
+            v = (8 + m) * 2.0 ** (e - 10)
+        t[c] = -v if c & 0x80 else v
+    return t
+
+
+_FP8_VALUES = _fp8_table()
+
+
+def f32_to_fp8_bits(x: np.ndarray) -> np.ndarray:
+    """Round to nearest (ties to even) onto e4m3, saturating at +-448; codes in the low byte of uint16 words."""
+    x = np.ascontiguousarray(x, dtype=np.float32).astype(np.float64)
+    a = np.minimum(np.abs(x), 448.0)
+    _, e = np.frexp(np.where(a > 0, a, 1.0))             # a = f * 2^e, f in [0.5, 1)
+    lead = np.maximum(e - 1, -6)                          # below 2^-6 the quantum is fixed (subnormal codes)
+    q = np.ldexp(1.0, lead - 3)
+    r = np.rint(a / q) * q                                # rint: ties to even
+    r = np.minimum(r, 448.0)
+    _, e2 = np.frexp(np.where(r > 0, r, 1.0))
+    normal = r >= 2.0 ** -6
+    expf = np.where(normal, e2 - 1 + 7, 0)
+    mant = np.where(normal, np.rint(r / np.ldexp(1.0, e2 - 1 - 3)) - 8, np.rint(r / 2.0 ** -9))
+    code = (expf.astype(np.int64) << 3) | mant.astype(np.int64)
+    code = np.where(np.signbit(x), code | 0x80, code)
+    return code.astype(np.uint16)
+
+
+def fp8_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return _FP8_VALUES[np.ascontiguousarray(b).astype(np.int64) & 0xFF]
+
+
 def to_bits(x: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == FP8:
+        return f32_to_fp8_bits(x)
     return f32_to_bf16_bits(x) if dtype == BF16 else f32_to_f16_bits(x)
 
 
 def from_bits(b: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == FP8:
+        return fp8_bits_to_f32(b)
     return bf16_bits_to_f32(b) if dtype == BF16 else f16_bits_to_f32(b)
 
 

@@ -47,6 +47,43 @@ def test_round_kv_matches_library_rne():
         assert OPS.round_kv(float(x), F16) == wh, x
 
 
+def test_round_kv_fp8_against_the_code_table_brute_force_and_torch():
+    """The 8-bit cache format (e4m3: 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest finite value
+    448).  Three references that share nothing with the oracle's rounding: the value of every code written out from
+    the format definition, a brute-force search for the nearest finite value (ties to the even mantissa), and
+    torch's float8_e4m3fn cast (which saturates nothing: compared inside the finite range only)."""
+    FP8 = synth.FP8
+    values = []
+    for code in range(256):
+        e, m = (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            assert np.isnan(OPS.upcast(code, FP8))
+            continue
+        v = (m * 2.0 ** -9) if e == 0 else (8 + m) * 2.0 ** (e - 10)
+        v = -v if code & 0x80 else v
+        assert OPS.upcast(code, FP8) == v
+        assert OPS.round_kv(v, FP8) == v                    # representable values are fixed points
+        values.append((v, m))
+    assert max(v for v, _ in values) == 448.0 and min(abs(v) for v, _ in values if v != 0) == 2.0 ** -9
+    finite = sorted(set(v for v, _ in values))
+    even = {v: (m % 2 == 0) for v, m in values}
+    xs = np.concatenate([RNG.standard_normal(3000) * 2, RNG.standard_normal(500) * 200, RNG.standard_normal(500) * 0.01,
+                         np.array([1.0625, 1.1875, -1.0625, 0.0009765625, 0.0029296875, 464.0, 463.9, 1e6, -1e6, 0.0,
+                                   2.0 ** -10, 3 * 2.0 ** -10, 17.0, 19.0])])
+    for x in xs:
+        got = OPS.round_kv(float(x), FP8)
+        d = [abs(v - x) for v in finite]
+        best = min(d)
+        near = [v for v, dd in zip(finite, d) if dd == best]
+        want = near[0] if len(near) == 1 else [v for v in near if even[v]][0]
+        assert got == want, (x, got, want)
+        assert synth.fp8_bits_to_f32(synth.f32_to_fp8_bits(np.array([x], np.float32)))[0] == OPS.round_kv(float(np.float32(x)), FP8)
+    inside = np.array([x for x in xs if abs(x) <= 448.0], np.float32)
+    want_t = torch.from_numpy(inside).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    for x, w in zip(inside, want_t):
+        assert OPS.round_kv(float(x), FP8) == w, x
+
+
 # --------------------------------------------------------------------------- operators
 @pytest.mark.parametrize("dtype", [F16, BF16])
 def test_rmsnorm_vs_torch_and_closed_form(dtype):
