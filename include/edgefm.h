@@ -29,7 +29,12 @@ extern "C" {
 
 typedef struct edgefm_model edgefm_model; /* opaque, library-owned host object */
 
-typedef enum { EDGEFM_F16 = 1, EDGEFM_BF16 = 2 } edgefm_dtype;
+/* Storage types.  EDGEFM_FP8_E4M3 is for kv_dtype only: the compressed cache of Section 3.9 in its simplest
+ * form, C(KV) = each element rounded to 8-bit e4m3 (4 exponent bits with bias 7, 3 mantissa bits, no infinities:
+ * values that would round beyond the largest finite value 448 are stored as 448; round to nearest, ties to even)
+ * and decompressed exactly where it is read.  The paper states C only as a transformation of the cache and
+ * leaves the choice open; this one halves the cache and needs no side information. */
+typedef enum { EDGEFM_F16 = 1, EDGEFM_BF16 = 2, EDGEFM_FP8_E4M3 = 3 } edgefm_dtype;
 
 typedef enum {
     EDGEFM_OK = 0,
@@ -47,7 +52,7 @@ typedef struct {
     uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab;
     uint32_t max_seq_len;          /* KV slot size, pre-allocated at load (Section 3.9) */
     float rms_eps, rope_theta;
-    uint32_t weight_dtype, kv_dtype; /* edgefm_dtype; embeddings passed to prefill use weight_dtype */
+    uint32_t weight_dtype, kv_dtype; /* edgefm_dtype (weights: the 16-bit types); embeddings passed to prefill use weight_dtype */
     uint32_t tie_embeddings;         /* 1: lm_head is the embedding matrix                           */
     uint32_t qkv_bias;               /* 1: bqkv present                                              */
 } edgefm_config;
@@ -162,13 +167,14 @@ int edgefm_last_hip_error(const edgefm_model *m);
 
 /* ---- test and measurement accessors (synchronise the stream) ---------------------------------- */
 
-/* Copy one cache position of one layer to the host: k, v are [n_kv_heads * head_dim] kv_dtype bits.
+/* Copy one cache position of one layer to the host: k, v are [n_kv_heads * head_dim] kv_dtype elements (two bytes
+ * each, one byte each for EDGEFM_FP8_E4M3).
  * Any pos < max_seq_len may be read (tests look for writes outside the valid range). */
 int edgefm_debug_kv_read(edgefm_model *m, uint32_t layer, uint32_t pos, void *k_host, void *v_host);
 /* Overwrite cache positions 0 .. n_pos-1 of one layer from host rows [n_pos, n_kv_heads * head_dim]. */
 int edgefm_debug_kv_write(edgefm_model *m, uint32_t layer, uint32_t n_pos, const void *k_host,
                           const void *v_host);
-/* Fill the whole KV slot with a 16-bit pattern (sentinel for indexing tests). */
+/* Fill the whole KV slot with a 16-bit pattern (sentinel for indexing tests; two elements of an 8-bit cache). */
 int edgefm_debug_kv_fill(edgefm_model *m, uint16_t pattern);
 /* Declare the first n positions valid (after edgefm_debug_kv_write on every layer). */
 int edgefm_debug_set_kv_len(edgefm_model *m, uint32_t n);

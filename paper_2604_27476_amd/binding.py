@@ -15,7 +15,7 @@ import numpy as np
 
 from .buildlib import lib_path
 
-EDGEFM_F16, EDGEFM_BF16 = 1, 2
+EDGEFM_F16, EDGEFM_BF16, EDGEFM_FP8_E4M3 = 1, 2, 3
 EDGEFM_PREFILL_F16, EDGEFM_PREFILL_F16X2 = 1, 2
 EDGEFM_OK = 0
 EDGEFM_ERR_INVALID_ARG, EDGEFM_ERR_ARENA_TOO_SMALL, EDGEFM_ERR_CONTEXT_OVERFLOW = -1, -2, -3
@@ -263,13 +263,16 @@ class Model:
         return out
 
     def kv_read(self, layer: int, pos: int):
+        """One cache position as storage codes in uint16 words (an 8-bit cache: the code in the low byte)."""
         n = self.cfg.n_kv_heads * self.cfg.head_dim
-        k = np.empty(n, dtype=np.uint16); v = np.empty(n, dtype=np.uint16)
+        et = np.uint8 if self.cfg.kv_dtype == EDGEFM_FP8_E4M3 else np.uint16
+        k = np.empty(n, dtype=et); v = np.empty(n, dtype=et)
         _check(self.lib.edgefm_debug_kv_read(self.h, layer, pos, _np_ptr(k), _np_ptr(v)), "edgefm_debug_kv_read")
-        return k, v
+        return k.astype(np.uint16), v.astype(np.uint16)
 
     def kv_write(self, layer: int, k_rows: np.ndarray, v_rows: np.ndarray):
-        k = np.ascontiguousarray(k_rows, dtype=np.uint16); v = np.ascontiguousarray(v_rows, dtype=np.uint16)
+        et = np.uint8 if self.cfg.kv_dtype == EDGEFM_FP8_E4M3 else np.uint16
+        k = np.ascontiguousarray(k_rows).astype(et); v = np.ascontiguousarray(v_rows).astype(et)
         _check(self.lib.edgefm_debug_kv_write(self.h, layer, k.shape[0], _np_ptr(k), _np_ptr(v)),
                "edgefm_debug_kv_write")
 

@@ -7,6 +7,7 @@ namespace efm {
 
 constexpr int DT_F16 = 1;   // IEEE binary16 storage
 constexpr int DT_BF16 = 2;  // bfloat16 storage
+constexpr int DT_FP8 = 3;   // 8-bit e4m3 storage (KV cache only): 4 exponent bits (bias 7), 3 mantissa bits, no infinities
 constexpr int WAVE = 64;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -65,6 +66,49 @@ template <int DT> __device__ __forceinline__ uint32_t down2(float lo, float hi) 
     return (uint32_t)down1<DT>(lo) | ((uint32_t)down1<DT>(hi) << 16);
 }
 
+// ---- KV-cache elements ---------------------------------------------------------------------------
+// The cache pointers are typed uint16_t everywhere; with DT_FP8 the same element offsets address bytes.
+// e4m3 code -> value.  (Exponent 15 with mantissa 7 is the format's NaN; the writer below never produces it.)
+__device__ __forceinline__ float fp8_up(uint32_t c) {
+    const uint32_t e = (c >> 3) & 15u, m = c & 7u;
+    const float a = e ? as_f32(((e + 120u) << 23) | (m << 20)) : (float)m * 0.001953125f;  // subnormal codes: m 2^-9
+    return (c & 0x80u) ? -a : a;
+}
+// value -> e4m3 code: round to nearest, ties to even; the format has no infinity, so what would round beyond
+// its largest finite value 448 stays at 448 (as does a NaN input).
+__device__ __forceinline__ uint32_t fp8_down(float f) {
+    const uint32_t sign = (as_u32(f) >> 24) & 0x80u;
+    const float a = fabsf(f);
+    uint32_t code;
+    if (!(a < 464.0f)) {
+        code = 0x7eu;
+    } else if (a < 0.015625f) {
+        code = (uint32_t)rintf(a * 512.0f);  // 0 .. 8 in units of 2^-9; 8 is the smallest normal code
+    } else {
+        uint32_t u = as_u32(a);
+        u += 0x7ffffu + ((u >> 20) & 1u);   // to 3 mantissa bits, ties to even; a carry moves into the exponent
+        code = (((u >> 23) - 120u) << 3) | ((u >> 20) & 7u);
+    }
+    return code | sign;
+}
+template <int KDT> __device__ __forceinline__ void cache_st1(uint16_t *cache, size_t at, float v) {
+    if constexpr (KDT == DT_FP8) reinterpret_cast<uint8_t *>(cache)[at] = (uint8_t)fp8_down(v);
+    else cache[at] = down1<KDT>(v);
+}
+// four adjacent elements (at a multiple of 4)
+template <int KDT> __device__ __forceinline__ void cache_st4(uint16_t *cache, size_t at, float a, float b, float c, float d) {
+    if constexpr (KDT == DT_FP8) {
+        *reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(cache) + at) =
+            fp8_down(a) | (fp8_down(b) << 8) | (fp8_down(c) << 16) | (fp8_down(d) << 24);
+    } else {
+        *reinterpret_cast<u32x2 *>(cache + at) = u32x2{down2<KDT>(a, b), down2<KDT>(c, d)};
+    }
+}
+template <int KDT> __device__ __forceinline__ float cache_ld1(const uint16_t *cache, size_t at) {
+    if constexpr (KDT == DT_FP8) return fp8_up(reinterpret_cast<const uint8_t *>(cache)[at]);
+    else return up1<KDT>(cache[at]);
+}
+
 // ---- loads ---------------------------------------------------------------------------------------
 // 128-bit streaming load: weights are read exactly once per step, so they should not displace the
 // activations and KV tiles that live in L2.
@@ -76,6 +120,27 @@ __device__ __forceinline__ gptr16 as_global16(const void *p) {
 }
 __device__ __forceinline__ u32x4 ld_stream16(const void *p) { return __builtin_nontemporal_load(as_global16(p)); }
 __device__ __forceinline__ u32x4 ld16(const void *p) { return *as_global16(p); }
+// eight adjacent cache elements (at a multiple of 8), raw; cache_unpack8 turns them into floats
+template <int KDT> __device__ __forceinline__ u32x4 cache_ld8(const uint16_t *cache, size_t at) {
+    if constexpr (KDT == DT_FP8) {
+        const u32x2 v = *reinterpret_cast<const __attribute__((address_space(1))) u32x2 *>(
+            reinterpret_cast<uintptr_t>(reinterpret_cast<const uint8_t *>(cache) + at));
+        return u32x4{v.x, v.y, 0u, 0u};
+    } else {
+        return ld16(cache + at);
+    }
+}
+template <int KDT> __device__ __forceinline__ void cache_unpack8(const u32x4 &v, float *f) {
+    if constexpr (KDT == DT_FP8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[e] = fp8_up((v.x >> (8 * e)) & 0xffu);
+            f[4 + e] = fp8_up((v.y >> (8 * e)) & 0xffu);
+        }
+    } else {
+        unpack8<KDT>(v, f);
+    }
+}
 
 // ---- two-term f16 operands of the prefill-side MFMAs ---------------------------------------------
 // split an fp32 value into two f16 terms: hi = f16(v), lo = f16(v - hi)

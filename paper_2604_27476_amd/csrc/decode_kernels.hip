@@ -77,13 +77,13 @@ k_qkv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const u
                 q[r0] = v0;
                 q[r1] = v1;
             } else if (hh < nq + nkv) {
-                uint16_t *dst = kc + ((size_t)(hh - nq) * max_seq + pos) * d;
-                dst[i] = down1<KDT>(v0);
-                dst[i + half] = down1<KDT>(v1);
+                const size_t at = ((size_t)(hh - nq) * max_seq + pos) * d;
+                cache_st1<KDT>(kc, at + i, v0);
+                cache_st1<KDT>(kc, at + i + half, v1);
             } else {
-                uint16_t *dst = vc + ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
-                dst[i] = down1<KDT>(v0);
-                dst[i + half] = down1<KDT>(v1);
+                const size_t at = ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
+                cache_st1<KDT>(vc, at + i, v0);
+                cache_st1<KDT>(vc, at + i + half, v1);
             }
         }
     }
@@ -374,8 +374,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
     }
-    const uint16_t *kbase = kc + (size_t)kvh * max_seq * D + li * 8;
-    const uint16_t *vbase = vc + (size_t)kvh * max_seq * D + li * 8;
+    const size_t row0 = (size_t)kvh * max_seq * D + li * 8;  // element offset of this lane's part of cache row 0
 
     for (int jb = j0 + wave * (RW * UR); jb < j1; jb += NW * RW * UR) {
         u32x4 kv[UR], vv[UR];
@@ -385,14 +384,14 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
             const int j = jb + u * RW + sub;
             ok[u] = j < j1;
             const int jj = ok[u] ? j : j0;  // any valid row; its score is discarded
-            kv[u] = ld16(kbase + (size_t)jj * D);
-            vv[u] = ld16(vbase + (size_t)jj * D);
+            kv[u] = cache_ld8<KDT>(kc, row0 + (size_t)jj * D);
+            vv[u] = cache_ld8<KDT>(vc, row0 + (size_t)jj * D);
         }
         float sc[UR][GQ];
 #pragma unroll
         for (int u = 0; u < UR; ++u) {
             float kf[8];
-            unpack8<KDT>(kv[u], kf);
+            cache_unpack8<KDT>(kv[u], kf);
 #pragma unroll
             for (int h = 0; h < GQ; ++h) {
                 float t = 0.f;
@@ -419,7 +418,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
 #pragma unroll
         for (int u = 0; u < UR; ++u) {
             float vf[8];
-            unpack8<KDT>(vv[u], vf);
+            cache_unpack8<KDT>(vv[u], vf);
 #pragma unroll
             for (int h = 0; h < GQ; ++h) {
                 const float p = sc[u][h];
@@ -602,6 +601,10 @@ hipError_t kernels_prepare(const Dims &D) {
     PREP((k_qkv<DT_BF16, DT_F16, 1>))
     PREP((k_qkv<DT_F16, DT_BF16, 1>))
     PREP((k_qkv<DT_F16, DT_F16, 1>))
+    PREP((k_qkv<DT_BF16, DT_FP8, 0>))
+    PREP((k_qkv<DT_F16, DT_FP8, 0>))
+    PREP((k_qkv<DT_BF16, DT_FP8, 1>))
+    PREP((k_qkv<DT_F16, DT_FP8, 1>))
 #undef PREP
     return hipSuccess;
 }
@@ -632,8 +635,10 @@ void launch_qkv(const Dims &D, const Geo &G, const LayerW &W, const float *x, co
         else QKV_LAUNCH1(WDT, KDT, 0);     \
     } while (0)
     if (D.wdt == DT_BF16 && D.kvdt == DT_BF16) QKV_LAUNCH(DT_BF16, DT_BF16);
+    else if (D.wdt == DT_BF16 && D.kvdt == DT_FP8) QKV_LAUNCH(DT_BF16, DT_FP8);
     else if (D.wdt == DT_BF16) QKV_LAUNCH(DT_BF16, DT_F16);
     else if (D.kvdt == DT_BF16) QKV_LAUNCH(DT_F16, DT_BF16);
+    else if (D.kvdt == DT_FP8) QKV_LAUNCH(DT_F16, DT_FP8);
     else QKV_LAUNCH(DT_F16, DT_F16);
 #undef QKV_LAUNCH
 #undef QKV_LAUNCH1
@@ -748,6 +753,9 @@ void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint1
     if (D.kvdt == DT_BF16) {
         if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
         else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+    } else if (D.kvdt == DT_FP8) {
+        if (D.d == 128) attn_launch_g<DT_FP8, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+        else attn_launch_g<DT_FP8, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
     } else {
         if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
         else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);

@@ -80,13 +80,13 @@ k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const
                 q[(size_t)m * qd + r0] = v0;
                 q[(size_t)m * qd + r1] = v1;
             } else if (hh < nq + nkv) {
-                uint16_t *dst = kc + ((size_t)(hh - nq) * max_seq + p) * d;
-                dst[i] = down1<KDT>(v0);
-                dst[i + half] = down1<KDT>(v1);
+                const size_t at = ((size_t)(hh - nq) * max_seq + p) * d;
+                cache_st1<KDT>(kc, at + i, v0);
+                cache_st1<KDT>(kc, at + i + half, v1);
             } else {
-                uint16_t *dst = vc + ((size_t)(hh - nq - nkv) * max_seq + p) * d;
-                dst[i] = down1<KDT>(v0);
-                dst[i + half] = down1<KDT>(v1);
+                const size_t at = ((size_t)(hh - nq - nkv) * max_seq + p) * d;
+                cache_st1<KDT>(vc, at + i, v0);
+                cache_st1<KDT>(vc, at + i + half, v1);
             }
         }
     }
@@ -300,7 +300,7 @@ void launch_qkv_m(const Dims &D, const Geo &G, int M, const LayerW &W, const flo
     M_SWITCH(M, hipLaunchKernelGGL((k_qkv_m<DT, KDT, M>), dim3(g.blocks), dim3(g.threads), lds, st, W.wqkv, bias,      \
                                    W.attn_norm, x, rope_cos, rope_sin, d_pos, q, kc, vc, D.H, D.nq, D.nkv, D.d,       \
                                    D.max_seq, D.eps);)
-    DT_SWITCH(D.wdt, if (D.kvdt == DT_BF16) { QKV_CALL(DT_BF16) } else { QKV_CALL(DT_F16) })
+    DT_SWITCH(D.wdt, if (D.kvdt == DT_BF16) { QKV_CALL(DT_BF16) } else if (D.kvdt == DT_FP8) { QKV_CALL(DT_FP8) } else { QKV_CALL(DT_F16) })
 #undef QKV_CALL
 }
 

@@ -63,7 +63,7 @@ bool valid_config(const edgefm_config *c) {
     if (g < 1 || g > 8) return false;
     if (c->hidden % 8 || c->intermediate % 8) return false;
     if ((c->weight_dtype != EDGEFM_F16 && c->weight_dtype != EDGEFM_BF16) ||
-        (c->kv_dtype != EDGEFM_F16 && c->kv_dtype != EDGEFM_BF16))
+        (c->kv_dtype != EDGEFM_F16 && c->kv_dtype != EDGEFM_BF16 && c->kv_dtype != EDGEFM_FP8_E4M3))
         return false;
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return false;
     // staged activation vectors must fit the 160 KB LDS of a CU with room for reduction scratch
@@ -105,8 +105,9 @@ void make_layout(const edgefm_config *c, Layout &L) {
     }
     L.rope_cos = take(Tm * (d / 2) * 4);
     L.rope_sin = take(Tm * (d / 2) * 4);
-    L.kcache = take(nl * kvd * Tm * 2);
-    L.vcache = take(nl * kvd * Tm * 2);
+    const size_t kv_esz = c->kv_dtype == EDGEFM_FP8_E4M3 ? 1 : 2;  // bytes per cache element
+    L.kcache = take(nl * kvd * Tm * kv_esz);
+    L.vcache = take(nl * kvd * Tm * kv_esz);
     L.x = take(H * 4);
     L.q = take(qd * 4);
     L.o = take(qd * 4);
@@ -189,8 +190,10 @@ struct edgefm_model {
     int *d_pos() const { return at<int>(L.ints); }
     int *d_token() const { return at<int>(L.ints) + 1; }
     int *d_next() const { return at<int>(L.ints) + 2; }
-    uint16_t *kc(int l) const { return at<uint16_t>(L.kcache) + (size_t)l * D.kvd() * D.max_seq; }
-    uint16_t *vc(int l) const { return at<uint16_t>(L.vcache) + (size_t)l * D.kvd() * D.max_seq; }
+    // Cache of layer l.  Typed uint16_t for every storage type; with the 8-bit type the kernels address bytes.
+    size_t kv_esz() const { return D.kvdt == DT_FP8 ? 1 : 2; }
+    uint16_t *kc(int l) const { return reinterpret_cast<uint16_t *>(arena + L.kcache + (size_t)l * D.kvd() * D.max_seq * kv_esz()); }
+    uint16_t *vc(int l) const { return reinterpret_cast<uint16_t *>(arena + L.vcache + (size_t)l * D.kvd() * D.max_seq * kv_esz()); }
     const uint16_t *lm() const { return at<uint16_t>(L.lm_head); }
 };
 
@@ -780,11 +783,12 @@ int edgefm_debug_kv_read(edgefm_model *m, uint32_t layer, uint32_t pos, void *k_
         return EDGEFM_ERR_INVALID_ARG;
     const Dims &D = m->D;
     HIPCHK(m, hipStreamSynchronize(m->stream));
+    const size_t esz = m->kv_esz(), row = (size_t)D.d * esz;
     for (int h = 0; h < D.nkv; ++h) {
-        const size_t off = ((size_t)h * D.max_seq + pos) * D.d;
-        HIPCHK(m, hipMemcpy(static_cast<uint16_t *>(k_host) + (size_t)h * D.d, m->kc(layer) + off, (size_t)D.d * 2,
+        const size_t off = ((size_t)h * D.max_seq + pos) * row;
+        HIPCHK(m, hipMemcpy(static_cast<char *>(k_host) + (size_t)h * row, reinterpret_cast<char *>(m->kc(layer)) + off, row,
                             hipMemcpyDeviceToHost));
-        HIPCHK(m, hipMemcpy(static_cast<uint16_t *>(v_host) + (size_t)h * D.d, m->vc(layer) + off, (size_t)D.d * 2,
+        HIPCHK(m, hipMemcpy(static_cast<char *>(v_host) + (size_t)h * row, reinterpret_cast<char *>(m->vc(layer)) + off, row,
                             hipMemcpyDeviceToHost));
     }
     return EDGEFM_OK;
@@ -796,12 +800,12 @@ int edgefm_debug_kv_write(edgefm_model *m, uint32_t layer, uint32_t n_pos, const
     const Dims &D = m->D;
     HIPCHK(m, hipStreamSynchronize(m->stream));
     // host rows are [pos][head][d]; the cache is [head][pos][d]
-    const size_t src_pitch = (size_t)D.kvd() * 2, row = (size_t)D.d * 2;
+    const size_t esz = m->kv_esz(), src_pitch = (size_t)D.kvd() * esz, row = (size_t)D.d * esz;
     for (int h = 0; h < D.nkv; ++h) {
-        HIPCHK(m, hipMemcpy2D(m->kc(layer) + (size_t)h * D.max_seq * D.d, row,
+        HIPCHK(m, hipMemcpy2D(reinterpret_cast<char *>(m->kc(layer)) + (size_t)h * D.max_seq * row, row,
                               static_cast<const char *>(k_host) + (size_t)h * row, src_pitch, row, n_pos,
                               hipMemcpyHostToDevice));
-        HIPCHK(m, hipMemcpy2D(m->vc(layer) + (size_t)h * D.max_seq * D.d, row,
+        HIPCHK(m, hipMemcpy2D(reinterpret_cast<char *>(m->vc(layer)) + (size_t)h * D.max_seq * row, row,
                               static_cast<const char *>(v_host) + (size_t)h * row, src_pitch, row, n_pos,
                               hipMemcpyHostToDevice));
     }
@@ -810,7 +814,7 @@ int edgefm_debug_kv_write(edgefm_model *m, uint32_t layer, uint32_t n_pos, const
 
 int edgefm_debug_kv_fill(edgefm_model *m, uint16_t pattern) {
     if (!m) return EDGEFM_ERR_INVALID_ARG;
-    const size_t n = (size_t)m->D.L * m->D.kvd() * m->D.max_seq;
+    const size_t n = (size_t)m->D.L * m->D.kvd() * m->D.max_seq * m->kv_esz() / 2;  // 16-bit words of one cache
     launch_fill_u16(m->at<uint16_t>(m->L.kcache), n, pattern, m->stream);
     launch_fill_u16(m->at<uint16_t>(m->L.vcache), n, pattern, m->stream);
     HIPCHK(m, hipStreamSynchronize(m->stream));

@@ -760,19 +760,20 @@ __global__ void k_rope_kv(const float *__restrict__ QKV, PipeRange P, const uint
             *reinterpret_cast<u32x2 *>(dst + q_stride + i) = u32x2{a0.lo, a1.lo};
             *reinterpret_cast<u32x2 *>(dst + q_stride + i + half) = u32x2{b0.lo, b1.lo};
         } else {
-            uint16_t *dst = hh < nq + nkv ? kc + ((size_t)(hh - nq) * max_seq + pos) * d
-                                          : vc + ((size_t)(hh - nq - nkv) * max_seq + pos) * d;
-            *reinterpret_cast<u32x2 *>(dst + i) = u32x2{down2<KDT>(v0[0], v0[1]), down2<KDT>(v0[2], v0[3])};
-            *reinterpret_cast<u32x2 *>(dst + i + half) = u32x2{down2<KDT>(v1[0], v1[1]), down2<KDT>(v1[2], v1[3])};
+            uint16_t *cache = hh < nq + nkv ? kc : vc;
+            const size_t at = ((size_t)(hh < nq + nkv ? hh - nq : hh - nq - nkv) * max_seq + pos) * d;
+            cache_st4<KDT>(cache, at + i, v0[0], v0[1], v0[2], v0[3]);
+            cache_st4<KDT>(cache, at + i + half, v1[0], v1[1], v1[2], v1[3]);
         }
     }
 }
 
-// Cache value -> f16 bits.  Every bf16 value of magnitude 2^-14 .. 65504 is an f16 value; smaller ones round
-// with an absolute error below 3e-8 and larger ones (never seen in a K or V row) saturate.
-template <int KDT> __device__ __forceinline__ uint16_t cache_to_f16(uint16_t b) {
-    if constexpr (KDT == DT_F16) return b;
-    const float v = fminf(fmaxf(up1<DT_BF16>(b), -65504.f), 65504.f);
+// Cache element -> f16 bits.  Every bf16 value of magnitude 2^-14 .. 65504 is an f16 value; smaller ones round
+// with an absolute error below 3e-8 and larger ones (never seen in a K or V row) saturate.  Every e4m3 value is
+// an f16 value.
+template <int KDT> __device__ __forceinline__ uint16_t cache_to_f16(const uint16_t *cache, size_t at) {
+    if constexpr (KDT == DT_F16) return cache[at];
+    const float v = fminf(fmaxf(cache_ld1<KDT>(cache, at), -65504.f), 65504.f);
     return down1<DT_F16>(v);
 }
 
@@ -793,13 +794,13 @@ k_prep_kv(const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc, int 
           uint16_t *__restrict__ Kf, uint16_t *__restrict__ Vt, int d, int max_seq) {
     __shared__ uint16_t tile[64][66];
     const int kvh = blockIdx.z, j0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
-    const uint16_t *ksrc = kc + (size_t)kvh * max_seq * d, *vsrc = vc + (size_t)kvh * max_seq * d;
+    const size_t src0 = (size_t)kvh * max_seq * d;
     uint16_t *kdst = Kf + (size_t)kvh * ctx_pad * d, *vdst = Vt + (size_t)kvh * d * ctx_pad;
     for (int e = threadIdx.x; e < 64 * 64; e += 256) {
         const int j = e >> 6, i = e & 63;
         const bool in = j0 + j < ctx;
-        kdst[(size_t)(j0 + j) * d + i0 + i] = in ? cache_to_f16<KDT>(ksrc[(size_t)(j0 + j) * d + i0 + i]) : (uint16_t)0;
-        tile[j][i] = in ? cache_to_f16<KDT>(vsrc[(size_t)(j0 + j) * d + i0 + i]) : (uint16_t)0;
+        kdst[(size_t)(j0 + j) * d + i0 + i] = in ? cache_to_f16<KDT>(kc, src0 + (size_t)(j0 + j) * d + i0 + i) : (uint16_t)0;
+        tile[j][i] = in ? cache_to_f16<KDT>(vc, src0 + (size_t)(j0 + j) * d + i0 + i) : (uint16_t)0;
     }
     __syncthreads();
     for (int e = threadIdx.x; e < 64 * 64; e += 256) {
@@ -1371,6 +1372,9 @@ void launch_rope_kv(const Dims &D, const float *QKV, int T, int p0, const float 
     if (D.kvdt == DT_BF16)
         hipLaunchKernelGGL(k_rope_kv<DT_BF16>, dim3((unsigned)blocks), dim3(threads), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
                            Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
+    else if (D.kvdt == DT_FP8)
+        hipLaunchKernelGGL(k_rope_kv<DT_FP8>, dim3((unsigned)blocks), dim3(threads), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
+                           Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
     else
         hipLaunchKernelGGL(k_rope_kv<DT_F16>, dim3((unsigned)blocks), dim3(threads), 0, st, QKV, pending, bias, D.wdt, T, p0, rope_cos, rope_sin,
                            Qs, q_stride, Qf, kc, vc, D.nq, D.nkv, D.d, D.max_seq);
@@ -1381,6 +1385,8 @@ void launch_prep_kv(const Dims &D, const uint16_t *kc, const uint16_t *vc, int c
     const dim3 grid(ctx_pad / 64, D.d / 64, D.nkv);
     if (D.kvdt == DT_BF16)
         hipLaunchKernelGGL(k_prep_kv<DT_BF16>, grid, dim3(256), 0, st, kc, vc, ctx, ctx_pad, Kf, Vt, D.d, D.max_seq);
+    else if (D.kvdt == DT_FP8)
+        hipLaunchKernelGGL(k_prep_kv<DT_FP8>, grid, dim3(256), 0, st, kc, vc, ctx, ctx_pad, Kf, Vt, D.d, D.max_seq);
     else
         hipLaunchKernelGGL(k_prep_kv<DT_F16>, grid, dim3(256), 0, st, kc, vc, ctx, ctx_pad, Kf, Vt, D.d, D.max_seq);
 }

@@ -91,10 +91,14 @@ class Pair:
         for l in layers:
             for p in positions:
                 kg, vg = self.gm.kv_read(l, p)
+                if kd == synth.FP8:   # the 16-bit fill pattern covers two elements: bytes 0xff and 0x7f, the NaN codes
+                    sk, sv = (kg & 0x7F) == 0x7F, (vg & 0x7F) == 0x7F
+                else:
+                    sk, sv = kg == SENTINEL, vg == SENTINEL
                 if p >= n:
-                    assert (kg == SENTINEL).all() and (vg == SENTINEL).all(), f"write beyond kv_len at layer {l} pos {p}"
+                    assert sk.all() and sv.all(), f"write beyond kv_len at layer {l} pos {p}"
                     continue
-                assert not (kg == SENTINEL).any() and not (vg == SENTINEL).any(), f"unwritten row layer {l} pos {p}"
+                assert not sk.any() and not sv.any(), f"unwritten row layer {l} pos {p}"
                 kg = synth.from_bits(kg, kd).astype(np.float64); vg = synth.from_bits(vg, kd).astype(np.float64)
                 ko, vo = self.om.kv_read(l, p)
                 assert rel_l2(kg, ko) < 1e-2 and rel_l2(vg, vo) < 1e-2, (l, p, rel_l2(kg, ko), rel_l2(vg, vo))
@@ -589,6 +593,43 @@ def test_short_block_attention_routes_agree(monkeypatch):
         assert flash.kv_len == o.kv_len == T
     flash.close()
     P.close()
+
+
+def test_fp8_kv_cache_tiny_and_7b_width():
+    """The compressed cache (Section 3.9) in the form this library defines it: every K and V element stored as
+    8-bit e4m3 (round to nearest even, saturating at 448) and read back exactly.  The oracle rounds the same way, so
+    the parity bar is the usual one.  Covers the cache writers (prefill RoPE kernel, decode and multi-position QKV
+    epilogues), the readers (decode attention with one and several queries, the f16 operand copies of the flash
+    kernel), indexing with the sentinel fill, roll-back, a verify block on each route and an injected long context."""
+    shape = synth.TINY.with_(name="tiny-fp8kv", weight_dtype=synth.BF16, kv_dtype=synth.FP8, qkv_bias=True, max_seq_len=150)
+    P = Pair(shape)
+    P.run(synth.make_prompt(shape, 40), 12)
+    assert P.gm.kv_len == 52
+    P.check_kv(range(shape.n_layers), [0, 1, 39, 40, 41, 51, 52, 53, 149])
+    rng = np.random.default_rng(31)
+    for m in (3, 8, 20):                                  # multi-vector GEMV route, GEMM route with decode attention, with flash
+        _check_verify(P, rng.integers(0, shape.vocab, size=m).astype(np.int32), f"fp8 cache verify m={m}")
+    P.check_kv([0, 1], [52, 54, 55, 62, 63, 82, 83])
+    P.om.kv_reset(45); P.gm.kv_reset(45)                  # roll back into the prompt's continuation and go on
+    P.prefill(synth.make_prompt(shape, 30, seed=2), where="fp8 cache: suffix on a kept prefix")
+    P.decode(9, "fp8 cache: decode after the suffix")
+    P.check_kv([0, 1], [44, 45, 74, 75, 149])            # 76..82 hold rows of the dropped blocks; 149 was never written
+    print(f"fp8 cache tiny worst {P.worst}")
+    P.close()
+    wide = synth.QWEN_7B.with_(name="7b-l2-fp8kv", vocab=4096, kv_dtype=synth.FP8, max_seq_len=1400)
+    P2 = Pair(wide, n_layers=2, sentinel=False)
+    ctx = 1000
+    rows = [synth.make_kv_rows(wide, l, ctx) for l in range(2)]
+    P2.om.kv_inject(rows)
+    for l, (k, v) in enumerate(rows):
+        P2.gm.kv_write(l, k, v)
+    P2.gm.set_kv_len(ctx)
+    tok = P2.decode(17, "fp8 cache, 7B width, injected context 1000, step 0")
+    P2.decode(tok, "fp8 cache, 7B width, step 1")
+    P2.prefill(synth.make_prompt(wide, 300, seed=4), where="fp8 cache, 7B width: 300 rows appended")
+    P2.check_kv([0, 1], [999, 1000, 1001, 1002, 1301])
+    print(f"fp8 cache 7B width worst {P2.worst}")
+    P2.close()
 
 
 def test_verify_step_7b_width_context_1000():
