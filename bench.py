@@ -143,7 +143,21 @@ def sweep(args) -> int:
                               "decode_ms_per_token_p50": round(float(np.percentile(dd, 50)), 4),
                               "decode_ms_per_token_p99": round(float(np.percentile(dd, 99)), 4), "repetitions": 100}), flush=True)
         gm.close()
-        del gm, w
+        del gm
+        if name == "qwen2.5-7b-shaped":  # the same decode with the 8-bit cache: half the cache bytes and slot size
+            shape8 = shape.with_(kv_dtype=synth.FP8)
+            gm8 = binding.Model(binding.make_config(shape8), w)
+            for C, N in decodes[-2:]:
+                prompt = synth.make_prompt(shape8, C)
+                ds = [timed_request(gm8, prompt, N)[1] for _ in range(1 + max(2, args.steps // 2))][1:]
+                ms = float(np.mean(ds))
+                byts = shape8.weight_bytes_per_token() + shape8.kv_bytes_per_context_token() // 2 * (C + (N - 1) / 2.0)
+                print(json.dumps({"shape": name, "kind": "decode_fp8_cache", "context": C, "decode_steps": N,
+                                  "ms_per_token": round(ms, 4), "hbm_GBps": round(byts / (ms * 1e-3) / 1e9, 1),
+                                  "arena_GB": round(gm8.arena_bytes / 1e9, 2)}), flush=True)
+            gm8.close()
+            del gm8
+        del w
     return 0
 
 

@@ -132,11 +132,15 @@ template <int KDT> __device__ __forceinline__ u32x4 cache_ld8(const uint16_t *ca
 }
 template <int KDT> __device__ __forceinline__ void cache_unpack8(const u32x4 &v, float *f) {
     if constexpr (KDT == DT_FP8) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            f[e] = fp8_up((v.x >> (8 * e)) & 0xffu);
-            f[4 + e] = fp8_up((v.y >> (8 * e)) & 0xffu);
-        }
+        // the hardware conversion (OCP e4m3 on gfx950) of one byte of a word; the selector has to be a constant
+        f[0] = __builtin_amdgcn_cvt_f32_fp8((int)v.x, 0);
+        f[1] = __builtin_amdgcn_cvt_f32_fp8((int)v.x, 1);
+        f[2] = __builtin_amdgcn_cvt_f32_fp8((int)v.x, 2);
+        f[3] = __builtin_amdgcn_cvt_f32_fp8((int)v.x, 3);
+        f[4] = __builtin_amdgcn_cvt_f32_fp8((int)v.y, 0);
+        f[5] = __builtin_amdgcn_cvt_f32_fp8((int)v.y, 1);
+        f[6] = __builtin_amdgcn_cvt_f32_fp8((int)v.y, 2);
+        f[7] = __builtin_amdgcn_cvt_f32_fp8((int)v.y, 3);
     } else {
         unpack8<KDT>(v, f);
     }
