@@ -45,9 +45,19 @@ def test_query_sizes_accounts_for_weights_and_kv(lib):
         assert n < 4 * (shape.weight_bytes_per_token() + kv) + (2 << 30)
 
 
+def test_query_sizes_halves_the_kv_slot_for_the_8_bit_cache(lib):
+    """kv_dtype = EDGEFM_FP8_E4M3: one byte per cache element, so the arena shrinks by exactly half of the two
+    16-bit caches (up to the 256-byte alignment of the buffers that follow)."""
+    for shape in (synth.TINY, synth.QWEN_7B):
+        n16 = binding.edgefm_query_sizes(binding.make_config(shape))
+        n8 = binding.edgefm_query_sizes(binding.make_config(shape.with_(kv_dtype=synth.FP8)))
+        saved = shape.max_seq_len * shape.kv_bytes_per_context_token() // 2
+        assert abs((n16 - n8) - saved) <= 2 * 256
+
+
 @pytest.mark.parametrize("field,value", [
     ("n_layers", 0), ("hidden", 0), ("hidden", 260), ("head_dim", 96), ("n_kv_heads", 3), ("n_q_heads", 18),
-    ("weight_dtype", 0), ("kv_dtype", 7), ("max_seq_len", 0), ("vocab", 0), ("intermediate", 100),
+    ("weight_dtype", 0), ("weight_dtype", 3), ("kv_dtype", 7), ("max_seq_len", 0), ("vocab", 0), ("intermediate", 100),
     ("hidden", 1 << 20),
 ])
 def test_query_sizes_rejects_unsupported_configs(lib, field, value):
