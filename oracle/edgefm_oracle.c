@@ -73,14 +73,6 @@ static double bits_to_double(uint16_t b, uint32_t dtype) {
         memcpy(&f, &u, 4);
         return (double)f;
     }
-    if (dtype == ORACLE_FP8) { /* sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent 15 with mantissa 7 is NaN */
-        int s8 = (b >> 7) & 1, e8 = (b >> 3) & 15, m8 = b & 7;
-        double v8;
-        if (e8 == 15 && m8 == 7) v8 = NAN;
-        else if (e8 == 0) v8 = ldexp((double)m8, -9);
-        else v8 = ldexp((double)(8 + m8), e8 - 10);
-        return s8 ? -v8 : v8;
-    }
     /* IEEE binary16 */
     int sign = (b >> 15) & 1, e = (b >> 10) & 31, m = b & 1023;
     double v;
@@ -88,6 +80,19 @@ static double bits_to_double(uint16_t b, uint32_t dtype) {
     else if (e == 31) v = m ? NAN : INFINITY;
     else v = ldexp((double)(m + 1024), e - 25);
     return sign ? -v : v;
+}
+
+/* Cache storage codes: the 16-bit formats above, or 8-bit e4m3 (code in the low byte): sign, 4 exponent bits
+ * (bias 7), 3 mantissa bits; exponent 15 with mantissa 7 is NaN, there are no infinities.  Kept apart from
+ * bits_to_double, which sits in the innermost loop of every matrix product. */
+static double cache_bits_to_double(uint16_t b, uint32_t dtype) {
+    if (dtype != ORACLE_FP8) return bits_to_double(b, dtype);
+    int s8 = (b >> 7) & 1, e8 = (b >> 3) & 15, m8 = b & 7;
+    double v8;
+    if (e8 == 15 && m8 == 7) v8 = NAN;
+    else if (e8 == 0) v8 = ldexp((double)m8, -9);
+    else v8 = ldexp((double)(8 + m8), e8 - 10);
+    return s8 ? -v8 : v8;
 }
 
 /* Round to nearest, ties to even, onto a binary format with `p` significand
@@ -114,7 +119,7 @@ double oracle_round_kv(double x, uint32_t dtype) {
     return round_to_format(x, 11, -14, 65504.0);
 }
 
-double oracle_upcast(uint16_t bits, uint32_t dtype) { return bits_to_double(bits, dtype); }
+double oracle_upcast(uint16_t bits, uint32_t dtype) { return cache_bits_to_double(bits, dtype); }
 
 /* ------------------------------------------------------------------ */
 /* Operators (Section 3.4 names them; the formulas are the standard    */
@@ -309,8 +314,8 @@ int oracle_kv_write(oracle_model *m, uint32_t layer, uint32_t n_pos, const uint1
             real *kr = cache_row(m->kcache, c, layer, h, p), *vr = cache_row(m->vcache, c, layer, h, p);
             for (uint32_t i = 0; i < c->head_dim; ++i) {
                 size_t s = ((size_t)p * c->n_kv_heads + h) * c->head_dim + i;
-                kr[i] = (real)bits_to_double(k[s], c->kv_dtype);
-                vr[i] = (real)bits_to_double(v[s], c->kv_dtype);
+                kr[i] = (real)cache_bits_to_double(k[s], c->kv_dtype);
+                vr[i] = (real)cache_bits_to_double(v[s], c->kv_dtype);
             }
         }
     return 0;
