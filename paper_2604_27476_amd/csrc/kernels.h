@@ -127,10 +127,25 @@ void launch_embed_rows(const Dims &D, const uint16_t *embed, const uint16_t *emb
 // A_hi[t] + A_lo[t] <- RMSNorm(X[t]) * gain
 void launch_rmsnorm_rows(const Dims &D, const float *X, const uint16_t *gain, int T, uint16_t *Ahi, uint16_t *Alo,
                          hipStream_t st);
-// dst <- f16(src * 2^8): the prefill copy of a weight tensor (n elements, multiple of 8)
-void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, size_t n, hipStream_t st);
+// Layout of the f16 prefill copy ("W16") of a weight matrix [N][K]: tiles of 256 rows x 32 values.  The 32 values of
+// a row are contiguous (64 bytes), then the 256 rows of a k-tile (16 KB), then the k-tiles of a row tile: everything
+// a GEMM workgroup reads for one column tile of its output is one contiguous range, walked front to back.  (From the
+// row-major matrix a k-tile is 256 pieces of 64 bytes, a row apart each; a weight stream made of such pieces reaches
+// two thirds of the rate of a contiguous one on this memory system, which is what a GEMM with few rows runs at.)
+// Row tile t holds rows 256 t .. 256 t + 255; for the gate | up matrix [2 I][K] of the SwiGLU GEMM it holds the gate
+// rows of neurons 128 t .. 128 t + 127 followed by the up rows of the same neurons (N = I there).  Rows beyond the
+// matrix and values beyond K are zero.
+constexpr int W16_TILE_ROWS = 256, W16_TILE_K = 32, W16_TILE_ELEMS = W16_TILE_ROWS * W16_TILE_K;
+__host__ __device__ inline int w16_row_tiles(int N, bool swiglu) { return swiglu ? (N + 127) / 128 : (N + 255) / 256; }
+__host__ __device__ inline int w16_k_tiles(int K) { return (K + W16_TILE_K - 1) / W16_TILE_K; }
+__host__ __device__ inline size_t w16_elems(int N, int K, bool swiglu) {
+    return (size_t)w16_row_tiles(N, swiglu) * w16_k_tiles(K) * W16_TILE_ELEMS;
+}
+// dst (w16_elems(N, K, swiglu) values) <- f16(src * 2^8) in that layout; src is [N][K], or [2 N][K] with swiglu.
+// K is a multiple of 8.
+void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, int N, int K, bool swiglu, hipStream_t st);
 enum GemmEpi { EPI_BIAS_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
-// C = (A_hi + A_lo)[T,K] W16[N,K]^T / 2^8 with an epilogue:
+// C = (A_hi + A_lo)[T,K] W16[N,K]^T / 2^8 (W16 in the tiled layout above) with an epilogue:
 //   EPI_BIAS_F32: out_f32[T,N] = C + bias      EPI_RESID: X[T,N] += C
 //   EPI_SWIGLU  : W16 is [2 I, K] (gate | up), out_hi + out_lo [T,I] = silu(C_gate) * C_up, N = I
 // ws: GEMM_WS_BYTES of scratch for the k-slices of split tiles (null: tiles are never split)

@@ -98,10 +98,10 @@ void make_layout(const edgefm_config *c, Layout &L) {
         L.mlp_norm[l] = take(H * 2);
         L.w_gate_up[l] = take(2 * I * H * 2);
         L.w_down[l] = take(H * I * 2);
-        L.p_wqkv[l] = take(R * H * 2);
-        L.p_wo[l] = take(H * qd * 2);
-        L.p_w_gate_up[l] = take(2 * I * H * 2);
-        L.p_w_down[l] = take(H * I * 2);
+        L.p_wqkv[l] = take(w16_elems((int)R, (int)H, false) * 2);
+        L.p_wo[l] = take(w16_elems((int)H, (int)qd, false) * 2);
+        L.p_w_gate_up[l] = take(w16_elems((int)I, (int)H, true) * 2);
+        L.p_w_down[l] = take(w16_elems((int)H, (int)I, false) * 2);
     }
     L.rope_cos = take(Tm * (d / 2) * 4);
     L.rope_sin = take(Tm * (d / 2) * 4);
@@ -144,7 +144,7 @@ void make_layout(const edgefm_config *c, Layout &L) {
     L.mo = take(MULTI_MAX * qd * 4);
     L.mh = take(MULTI_MAX * I * 4);
     L.mhidden = take(MULTI_MAX * H * 4);
-    L.p_lm = take(V * H * 2);
+    L.p_lm = take(w16_elems((int)V, (int)H, false) * 2);
     L.vlogits = take((size_t)VERIFY_MAX * V * 4);
     L.vgather = take((size_t)VERIFY_MAX * V * 4);
     L.vnext = take(VERIFY_MAX * 4);
@@ -434,7 +434,7 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
     LOADCHK(cp(m->L.embed, w->embed, V * H * 2));
     if (!cfg->tie_embeddings) LOADCHK(cp(m->L.lm_head, w->lm_head, V * H * 2));
     LOADCHK(cp(m->L.final_norm, w->final_norm, H * 2));
-    launch_convert_w16(D, m->lm(), m->at<uint16_t>(m->L.p_lm), V * H, m->stream);  // after the copies above, same stream
+    launch_convert_w16(D, m->lm(), m->at<uint16_t>(m->L.p_lm), D.V, D.H, false, m->stream);  // after the copies above, same stream
     m->LW.resize(D.L);
     m->PW.resize(D.L);
     for (int l = 0; l < D.L; ++l) {
@@ -454,10 +454,10 @@ int edgefm_model_load(const edgefm_config *cfg, const edgefm_weights *w, void *a
         lw.w_gate_up = m->at<uint16_t>(m->L.w_gate_up[l]);
         lw.w_down = m->at<uint16_t>(m->L.w_down[l]);
         // f16 copies for the prefill GEMMs, converted from the arena copies (same stream: ordered)
-        launch_convert_w16(D, lw.wqkv, m->at<uint16_t>(m->L.p_wqkv[l]), R * H, m->stream);
-        launch_convert_w16(D, lw.wo, m->at<uint16_t>(m->L.p_wo[l]), H * qd, m->stream);
-        launch_convert_w16(D, lw.w_gate_up, m->at<uint16_t>(m->L.p_w_gate_up[l]), 2 * I * H, m->stream);
-        launch_convert_w16(D, lw.w_down, m->at<uint16_t>(m->L.p_w_down[l]), H * I, m->stream);
+        launch_convert_w16(D, lw.wqkv, m->at<uint16_t>(m->L.p_wqkv[l]), D.R(), D.H, false, m->stream);
+        launch_convert_w16(D, lw.wo, m->at<uint16_t>(m->L.p_wo[l]), D.H, D.qd(), false, m->stream);
+        launch_convert_w16(D, lw.w_gate_up, m->at<uint16_t>(m->L.p_w_gate_up[l]), D.I, D.H, true, m->stream);
+        launch_convert_w16(D, lw.w_down, m->at<uint16_t>(m->L.p_w_down[l]), D.H, D.I, false, m->stream);
         m->PW[l].wqkv = m->at<uint16_t>(m->L.p_wqkv[l]);
         m->PW[l].wo = m->at<uint16_t>(m->L.p_wo[l]);
         m->PW[l].w_gate_up = m->at<uint16_t>(m->L.p_w_gate_up[l]);

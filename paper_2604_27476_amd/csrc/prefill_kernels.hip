@@ -81,16 +81,34 @@ __global__ void k_rmsnorm_rows(const float *__restrict__ X, const uint16_t *__re
 
 // f16 copy of a weight tensor, scaled by 2^8 (exact power of two, undone in the GEMM epilogue)
 constexpr float W16_SCALE = 256.0f;
+// One thread per 16-byte vector of the tiled copy (the layout is described in kernels.h): vector id =
+// ((row tile * k-tiles + k-tile) * 256 + row in tile) * 4 + chunk.
 template <int DT>
-__global__ void k_convert_w16(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, size_t nvec) {
+__global__ void k_convert_w16(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int N, int K, int swiglu,
+                              size_t nvec) {
+    const int nkt = w16_k_tiles(K);
     for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (size_t)gridDim.x * blockDim.x) {
-        float f[8];
-        unpack8<DT>(ld16(src + 8 * v), f);
-        u32x4 o;
-        o.x = down2<DT_F16>(f[0] * W16_SCALE, f[1] * W16_SCALE);
-        o.y = down2<DT_F16>(f[2] * W16_SCALE, f[3] * W16_SCALE);
-        o.z = down2<DT_F16>(f[4] * W16_SCALE, f[5] * W16_SCALE);
-        o.w = down2<DT_F16>(f[6] * W16_SCALE, f[7] * W16_SCALE);
+        const int c = (int)(v & 3), local = (int)((v >> 2) & 255);
+        const size_t blk = v >> 10;
+        const int kt = (int)(blk % nkt), tile = (int)(blk / nkt);
+        const int k = kt * W16_TILE_K + c * 8;
+        long long row;  // source row, or -1 for the padding
+        if (swiglu) {
+            const int j = tile * 128 + (local & 127);
+            row = j < N ? (long long)(local >> 7) * N + j : -1;
+        } else {
+            const int n = tile * 256 + local;
+            row = n < N ? n : -1;
+        }
+        u32x4 o = {0u, 0u, 0u, 0u};
+        if (row >= 0 && k < K) {
+            float f[8];
+            unpack8<DT>(ld16(src + (size_t)row * K + k), f);
+            o.x = down2<DT_F16>(f[0] * W16_SCALE, f[1] * W16_SCALE);
+            o.y = down2<DT_F16>(f[2] * W16_SCALE, f[3] * W16_SCALE);
+            o.z = down2<DT_F16>(f[4] * W16_SCALE, f[5] * W16_SCALE);
+            o.w = down2<DT_F16>(f[6] * W16_SCALE, f[7] * W16_SCALE);
+        }
         *reinterpret_cast<u32x4 *>(dst + 8 * v) = o;
     }
 }
@@ -139,22 +157,28 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
     }
     const int m0 = mt * BM;
 
-    // Global source row of LDS row r of the B tile, or -1 if outside the matrix.  With the SwiGLU epilogue a
-    // wave's WN columns are WN/2 gate columns followed by the WN/2 up columns of the same neurons, so that
-    // gate and up of a neuron meet in one lane: the workgroup covers BN/2 neurons.
-    auto brow = [&](int r) -> int {
+    // Where LDS row r of the B tile sits in the tiled weight copy (row tile and row inside it), or false if it
+    // is outside the matrix.  With the SwiGLU epilogue a wave's WN columns are WN/2 gate columns followed by the
+    // WN/2 up columns of the same neurons, so that gate and up of a neuron meet in one lane: the workgroup
+    // covers BN/2 neurons.
+    auto bloc = [&](int r, int &tile, int &local) -> bool {
         if constexpr (EPI == EPI_SWIGLU) {
             const int w = r / WN, rr = r % WN, up = rr / (WN / 2), c = rr % (WN / 2);
-            const int j = nb * (BN / 2) + w * (WN / 2) + c;
-            return j < N ? up * N + j : -1;  // N = I; gate rows [0,I), up rows [I,2I)
+            const int j = nb * (BN / 2) + w * (WN / 2) + c;  // N = I; gate rows [0,I), up rows [I,2I)
+            tile = j >> 7;
+            local = up * 128 + (j & 127);
+            return j < N;
         } else {
             const int n = nb * BN + r;
-            return n < N ? n : -1;
+            tile = n >> 8;
+            local = n & 255;
+            return n < N;
         }
     };
+    const int nkt = w16_k_tiles(K);
 
     // vector id = tid + 256*i -> (row, kvec): 8 consecutive threads read 128 contiguous bytes of a row
-    uint32_t oa[NA], ob[NB];  // element offsets (every operand here has fewer than 2^31 elements)
+    uint32_t oa[NA], ob[NB];  // element offsets (every operand here has fewer than 2^32 elements)
     bool va[NA], vb[NB];
     int sa[NA], sb[NB];
 #pragma unroll
@@ -168,9 +192,10 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int vid = tid + 256 * i, r = vid >> 3, kv = vid & 7;
-        const int br = brow(r);
-        vb[i] = br >= 0;
-        ob[i] = (uint32_t)(vb[i] ? br : 0) * (uint32_t)K + kv * 8;
+        int tile, local;
+        vb[i] = bloc(r, tile, local);
+        // the 64 values of a row that this k-step covers are two 64-byte pieces, one k-tile (16 KB) apart
+        ob[i] = vb[i] ? (uint32_t)((((size_t)tile * nkt + (kv >> 2)) * W16_TILE_ROWS + local) * W16_TILE_K + (kv & 3) * 8) : 0u;
         sb[i] = r * LDK + kv * 8;
     }
     u32x4 rah[NA], ral[NA], rb[NB];
@@ -185,7 +210,7 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
             if (two) ral[i] = (va[i] && kin) ? ld16(Alo + oa[i] + k0) : zero;
         }
 #pragma unroll
-        for (int i = 0; i < NB; ++i) rb[i] = (vb[i] && kin) ? ld16(W + ob[i] + k0) : zero;
+        for (int i = 0; i < NB; ++i) rb[i] = (vb[i] && kin) ? ld16(W + ob[i] + (size_t)k0 * W16_TILE_ROWS) : zero;
     };
     auto sstore = [&]() {
 #pragma unroll
@@ -289,10 +314,12 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 // ds_write) through a ring of three stages, two to three k-tiles ahead of the MFMAs, with one barrier per
 // k-tile.  LDS rows are 64 bytes (4 chunks of 16 B); chunk c of row r sits in slot c ^ ((r >> 1) & 3),
 // which makes both the 1 KB wave-wide DMA writes and the 128-bit fragment reads conflict-free.
-// Rows beyond T or N are clamped to the last valid row (their products are never stored).
+// Rows beyond T are clamped to the last valid row, rows beyond N are zero in the stored weight tiles (their
+// products are never stored).
 // ------------------------------------------------------------------------------------------------
 constexpr int PK = 32;                     // k-tile depth
-constexpr int P_STAGES = 3;
+constexpr int P_STAGES = 3;                // ring depth (six stages for the 64-row tiles measured slower: the
+                                           // larger ring leaves no room for a second workgroup on the CU)
 constexpr int P_BN = 256;                  // tile columns; tile rows are 64 WM
 constexpr int pipe_stage_elems(int wm, int terms) { return (terms * 64 * wm + P_BN) * PK; }  // A_hi | (A_lo) | B, f16 elements per stage
 constexpr int PIPE_MAX_SPLITS = 8;          // k-slices per tile at most (twice that for the 64-row tiles)
@@ -322,17 +349,33 @@ __device__ __forceinline__ void lds_dma16(const uint16_t *base, uint32_t voff, u
 __device__ __forceinline__ uint32_t lds_addr(const void *p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p));
 }
+// s_waitcnt vmcnt(min(tiles, MAXT) * PER_TILE): the wave goes on once at most that many of its vector-memory
+// operations (the youngest ones) are outstanding.  `tiles` must be wave-uniform.
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+template <int PER_TILE, int MAXT> __device__ __forceinline__ void wait_vm_tiles(int tiles) {
+    static_assert(MAXT >= 1 && MAXT <= 4, "written out for rings of three to six stages");
+    if constexpr (MAXT >= 4) if (tiles >= 4) return wait_vm<4 * PER_TILE>();
+    if constexpr (MAXT >= 3) if (tiles >= 3) return wait_vm<3 * PER_TILE>();
+    if constexpr (MAXT >= 2) if (tiles >= 2) return wait_vm<2 * PER_TILE>();
+    if (tiles >= 1) return wait_vm<PER_TILE>();
+    wait_vm<0>();
+}
 
-template <int BDT, int EPI, int WM, int TERMS>
-__global__ void __launch_bounds__(512)
+template <int BDT, int EPI, int WM, int TERMS, int TM = 2>
+__global__ void __launch_bounds__(512, WM == 1 ? 4 : 2)  // 64-row tiles: two workgroups per CU (128 registers per lane)
 k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const uint16_t *__restrict__ W, int T,
             int N, int K, const uint16_t *__restrict__ bias, float *__restrict__ outf, uint16_t *__restrict__ ohi,
             uint16_t *__restrict__ olo, PipeRange R) {
-    constexpr int TM = 2, TN = WM, WN = 32 * TN, WNW = 8 / WM;  // wave tile 64 x WN, waves WM x WNW
+    constexpr int TN = WM, WN = 32 * TN, WNW = 8 / WM;  // wave tile 32 TM x WN, waves WM x WNW
+    // TM = 1 (64-row tiles only): the block has at most 32 rows and the lower half of the tile is left out
+    // altogether -- not loaded, not read, not multiplied.  With eight waves side by side every wave reads the
+    // whole A tile from LDS, and a k-loop that only streams weights runs at the pace of those reads.
+    static_assert(TM == 2 || (TM == 1 && WM == 1), "half tiles exist for the 64-row shape only");
     constexpr int BM = 64 * WM, STAGE_ELEMS = pipe_stage_elems(WM, TERMS);
     constexpr int B_AT = TERMS * BM * PK;  // element offset of the B tile inside a stage
     static_assert(WNW * WN == P_BN, "the waves of a row have to cover the tile columns");
-    extern __shared__ __attribute__((aligned(1024))) uint16_t ring[];  // P_STAGES x (A_hi, A_lo if TERMS == 2, B)
+    constexpr int S = P_STAGES;
+    extern __shared__ __attribute__((aligned(1024))) uint16_t ring[];  // S x (A_hi, A_lo if TERMS == 2, B)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WNW, wn = wave % WNW;
@@ -352,22 +395,24 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         nk = (int)((long long)(split + 1) * nk_all / R.k_splits) - kbeg;
         Ahi += (size_t)kbeg * PK;
         if constexpr (TERMS == 2) Alo += (size_t)kbeg * PK;
-        W += (size_t)kbeg * PK;
+        // the weights are stored by tiles (kernels.h): column tile nb of the output is row tile nb of the copy,
+        // one contiguous range of nk_all blocks of 256 rows x PK values
+        W += ((size_t)nb * nk_all + kbeg) * W16_TILE_ELEMS;
     }
-    auto brow = [&](int r) -> int {  // global weight row of B-tile row r (clamped inside the matrix)
+    static_assert(PK == W16_TILE_K && P_BN == W16_TILE_ROWS, "a B tile of the kernel is a tile of the weight copy");
+    auto brow = [&](int r) -> int {  // row of B-tile row r inside the stored tile (rows beyond the matrix are zero there)
         if constexpr (EPI == EPI_SWIGLU) {
             const int w = r / WN, rr = r % WN, up = rr / (WN / 2), c = rr % (WN / 2);
-            const int j = min(nb * (P_BN / 2) + w * (WN / 2) + c, N - 1);
-            return up * N + j;
+            return up * (P_BN / 2) + w * (WN / 2) + c;
         } else {
-            return min(nb * P_BN + r, N - 1);
+            return r;
         }
     };
     // DMA plan: one instruction moves 16 rows x 64 B.  Wave w issues, per stage, instructions A_I w .. A_I w + A_I - 1
     // of the two A tiles and 2w, 2w + 1 of the B tile.  Lane l of an instruction covers row R0 + l/4, slot l%4,
     // i.e. logical chunk (l%4) ^ ((row >> 1) & 3).
     // With WM = 1 the two A tiles are 4 instructions each: waves 0-3 take one of A_hi, waves 4-7 one of A_lo
-    // (none with TERMS = 1).
+    // (none with TERMS = 1); with TM = 1 only the first two instructions of each exist.
     constexpr int A_I = BM >= 128 ? BM / 128 : 1, B_I = P_BN / 128;
     constexpr bool A_SPLIT = BM < 128;  // a wave loads from one of the two A tiles only
     uint32_t ga[A_I], gb[B_I];  // byte offsets of this lane's chunk at k0 = 0 (A_hi and A_lo share ga)
@@ -384,15 +429,19 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     for (int i = 0; i < B_I; ++i) {
         const int r = 16 * (B_I * wave + i) + (lane >> 2);
         const int c = (lane & 3) ^ ((r >> 1) & 3);
-        gb[i] = ((uint32_t)brow(r) * (uint32_t)K + c * 8) * 2u;
+        gb[i] = ((uint32_t)brow(r) * (uint32_t)PK + c * 8) * 2u;
         lb[i] = 16 * (B_I * wave + i) * PK * 2;
     }
+    // does this wave issue an A instruction at all (always, unless a wave loads from one A tile only)
+    const bool a_wave = !A_SPLIT || ((wave < 4 || TERMS == 2) && 16 * (wave & 3) < 32 * TM);
     auto issue = [&](int kt) {
-        const uint32_t st = lds_addr(ring) + (kt % P_STAGES) * (STAGE_ELEMS * 2);
+        const uint32_t st = lds_addr(ring) + (kt % S) * (STAGE_ELEMS * 2);
         const int k0 = kt * PK;
         if constexpr (A_SPLIT) {
-            if (wave < 4) lds_dma16(Ahi + k0, ga[0], st + la[0]);
-            else if constexpr (TERMS == 2) lds_dma16(Alo + k0, ga[0], st + BM * PK * 2 + la[0]);
+            if (a_wave) {
+                if (wave < 4) lds_dma16(Ahi + k0, ga[0], st + la[0]);
+                else lds_dma16(Alo + k0, ga[0], st + BM * PK * 2 + la[0]);
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < A_I; ++i) {
@@ -401,7 +450,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
             }
         }
 #pragma unroll
-        for (int i = 0; i < B_I; ++i) lds_dma16(W + k0, gb[i], st + B_AT * 2 + lb[i]);
+        for (int i = 0; i < B_I; ++i) lds_dma16(W + (size_t)kt * W16_TILE_ELEMS, gb[i], st + B_AT * 2 + lb[i]);
     };
 
     f32x16 acc[TM][TN];
@@ -418,7 +467,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         u32x4 ah[TM], al[TM], b[TN];
     };
     auto read_frag = [&](Frag &f, int kt, int ks) {
-        const uint16_t *st = ring + (kt % P_STAGES) * STAGE_ELEMS;
+        const uint16_t *st = ring + (kt % S) * STAGE_ELEMS;
 #pragma unroll
         for (int t = 0; t < TM; ++t) {
             const int r = wm * 64 + t * 32 + fr;
@@ -445,7 +494,7 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
                 for (int b = 0; b < TN; ++b) acc[a][b] = mfma32<DT_F16>(f.al[a], f.b[b], acc[a][b]);
         }
     };
-    static_assert(PK == 32 && P_STAGES == 3, "the schedule below is written for two k-steps per tile and a ring of three");
+    static_assert(PK == 32 && S >= 3, "the schedule below is written for two k-steps per tile and a ring of at least three");
     // Schedule: the eight waves form two groups of four (one wave of each group per SIMD) that alternate
     // between a memory phase (LDS-DMA issue, fragment reads of a whole k-tile) and a compute phase (the 32
     // MFMAs of that k-tile).  The groups run one phase apart, so in every phase each SIMD has one wave that
@@ -453,31 +502,29 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
     // hands the roles over.  Phase q ends with barrier q; group 0 reads tile kt in phase 2kt and multiplies in
     // phase 2kt+1, group 1 reads it in phase 2kt+1 and multiplies in phase 2kt+2.  Only the reading group issues
     // LDS-DMA (an issue costs its wave about 16 cycles per KB moved, which would otherwise delay MFMAs): each
-    // wave loads its share of tile kt+2 at the start of the phase in which it reads tile kt.  The stage that
+    // wave loads its share of tile kt+S-1 at the start of the phase in which it reads tile kt.  The stage that
     // receives it held tile kt-1, which both groups finished reading before barrier 2kt-1; every share of
-    // tile kt+2 has landed before barrier 2kt+3.
+    // tile kt+1 has landed before barrier 2kt+1 (results return in issue order: a wave that lets only its
+    // shares of the tiles behind kt+1 stay outstanding has tile kt+1 in LDS).
     const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);
     Frag f0, f1;
-    issue(0);
-    if (nk > 1) issue(1);
-    // this wave's LDS-DMA instructions per k-tile (with WM = 1 and one term, waves 4-7 issue one fewer)
+#pragma unroll
+    for (int t = 0; t < S - 1; ++t)
+        if (t < nk) issue(t);
+    // this wave's LDS-DMA instructions per k-tile (a wave without an A instruction issues B_I)
     constexpr int NI = (A_SPLIT ? 1 : TERMS * A_I) + B_I;
-    constexpr bool NI_BY_WAVE = A_SPLIT && TERMS == 1;
-    static_assert(NI == 6 || NI == 4 || NI == 3, "the vmcnt immediates below are written for these shapes");
-#define WAIT_ALL_BUT_ONE_TILE(extra)                                                        \
-    do {                                                                                    \
-        if constexpr (NI == 6) asm volatile("s_waitcnt vmcnt(6)" extra ::: "memory");       \
-        else if constexpr (NI == 4) asm volatile("s_waitcnt vmcnt(4)" extra ::: "memory");  \
-        else if (!NI_BY_WAVE || wave < 4) asm volatile("s_waitcnt vmcnt(3)" extra ::: "memory"); \
-        else asm volatile("s_waitcnt vmcnt(2)" extra ::: "memory");                         \
-    } while (0)
-    if (nk > 1) WAIT_ALL_BUT_ONE_TILE("");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    static_assert((S - 2) * NI < 64, "vmcnt is a six-bit counter");
+    // wait until at most `tiles` of this wave's k-tile shares (the youngest ones) are still in flight
+    auto wait_tiles = [&](int tiles) {
+        if (a_wave) wait_vm_tiles<NI, S - 2>(tiles);
+        else wait_vm_tiles<B_I, S - 2>(tiles);
+    };
+    wait_tiles(min(S - 1, nk) - 1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (grp == 0) {
         for (int kt = 0; kt < nk; ++kt) {
-            if (kt + 2 < nk) issue(kt + 2);
+            if (kt + S - 1 < nk) issue(kt + S - 1);
             read_frag(f0, kt, 0);
             read_frag(f1, kt, 1);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -487,9 +534,8 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
             mfma_frag(f0);
             mfma_frag(f1);
             __builtin_amdgcn_sched_barrier(0);
-            // this wave's share of tile kt+1 has landed; only tile kt+2 may still be in flight
-            if (kt + 2 < nk) WAIT_ALL_BUT_ONE_TILE("");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // this wave's share of tile kt+1 has landed; only the tiles behind it may still be in flight
+            wait_tiles(max(min(nk - kt - 2, S - 2), 0));
             __builtin_amdgcn_s_barrier();  // barrier 2kt+1
             asm volatile("" ::: "memory");
         }
@@ -497,11 +543,11 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         __builtin_amdgcn_s_barrier();  // barrier 0
         asm volatile("" ::: "memory");
         for (int kt = 0; kt < nk; ++kt) {
-            if (kt + 2 < nk) issue(kt + 2);
+            if (kt + S - 1 < nk) issue(kt + S - 1);
             read_frag(f0, kt, 0);
             read_frag(f1, kt, 1);
-            if (kt + 2 < nk) WAIT_ALL_BUT_ONE_TILE(" lgkmcnt(0)");
-            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            wait_tiles(max(min(nk - kt - 2, S - 2), 0));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();  // barrier 2kt+1
             __builtin_amdgcn_sched_barrier(0);
@@ -515,7 +561,6 @@ k_gemm_pipe(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, 
         }
     }
 
-#undef WAIT_ALL_BUT_ONE_TILE
     constexpr float UNSCALE = 1.0f / W16_SCALE;
     if (R.k_splits > 1) {  // partial sums of this k-slice, tile-local [BM][256] fp32
         float *wt = R.ws + (size_t)(split * R.n_tiles + tl) * (BM * P_BN);
@@ -1152,14 +1197,14 @@ void launch_rmsnorm_rows(const Dims &D, const float *X, const uint16_t *gain, in
         hipLaunchKernelGGL(k_rmsnorm_rows<DT_F16>, dim3(T), dim3(256), 0, st, X, gain, Ahi, Alo, D.H, D.eps);
 }
 
-void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, size_t n, hipStream_t st) {
-    const size_t nvec = n / 8;
+void launch_convert_w16(const Dims &D, const uint16_t *src, uint16_t *dst, int N, int K, bool swiglu, hipStream_t st) {
+    const size_t nvec = w16_elems(N, K, swiglu) / 8;
     size_t blocks = (nvec + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     if (D.wdt == DT_BF16)
-        hipLaunchKernelGGL(k_convert_w16<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, nvec);
+        hipLaunchKernelGGL(k_convert_w16<DT_BF16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, N, K, swiglu ? 1 : 0, nvec);
     else
-        hipLaunchKernelGGL(k_convert_w16<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, nvec);
+        hipLaunchKernelGGL(k_convert_w16<DT_F16>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, N, K, swiglu ? 1 : 0, nvec);
 }
 
 template <int BDT, int TM, int TN>
@@ -1185,10 +1230,13 @@ static bool gemm_pipe_enabled() {
     if (state < 0) {
         const char *e = getenv("EDGEFM_GEMM");
         bool ok = !(e && e[0] == 't');
-#define PIPE_ATTR1(BDT, EPI, WM, TERMS)                                                                        \
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pipe<BDT, EPI, WM, TERMS>),         \
+#define PIPE_ATTR2(BDT, EPI, WM, TERMS, TM)                                                                    \
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pipe<BDT, EPI, WM, TERMS, TM>),     \
                                    hipFuncAttributeMaxDynamicSharedMemorySize,                                 \
                                    P_STAGES * pipe_stage_elems(WM, TERMS) * 2) == hipSuccess;
+#define PIPE_ATTR1(BDT, EPI, WM, TERMS)                \
+    PIPE_ATTR2(BDT, EPI, WM, TERMS, 2)                 \
+    if constexpr (WM == 1) { PIPE_ATTR2(BDT, EPI, 1, TERMS, 1) }
 #define PIPE_ATTR(BDT, EPI, WM) PIPE_ATTR1(BDT, EPI, WM, 1) PIPE_ATTR1(BDT, EPI, WM, 2)
 #define PIPE_ATTR_EPI(BDT, WM) PIPE_ATTR(BDT, EPI_SWIGLU, WM) PIPE_ATTR(BDT, EPI_RESID, WM) PIPE_ATTR(BDT, EPI_BIAS_F32, WM)
         PIPE_ATTR_EPI(DT_BF16, 4) PIPE_ATTR_EPI(DT_BF16, 2) PIPE_ATTR_EPI(DT_BF16, 1)
@@ -1196,6 +1244,7 @@ static bool gemm_pipe_enabled() {
 #undef PIPE_ATTR_EPI
 #undef PIPE_ATTR
 #undef PIPE_ATTR1
+#undef PIPE_ATTR2
         state = ok ? 1 : 0;
     }
     return state == 1;
@@ -1223,12 +1272,22 @@ static void pipe_launch_terms(int epi, const uint16_t *Ahi, const uint16_t *Alo,
     const int per_xcd = (R.n_tiles * R.k_splits + N_XCD - 1) / N_XCD;
     const dim3 grid(per_xcd * N_XCD), block(512);
     const size_t lds = (size_t)P_STAGES * pipe_stage_elems(WM, TERMS) * 2;
-    if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
-    else if (epi == EPI_RESID)
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
-    else
-        hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32, WM, TERMS>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);
+#define PIPE_GO(TM)                                                                                                    \
+    do {                                                                                                               \
+        if (epi == EPI_SWIGLU)                                                                                         \
+            hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_SWIGLU, WM, TERMS, TM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);   \
+        else if (epi == EPI_RESID)                                                                                     \
+            hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_RESID, WM, TERMS, TM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R);    \
+        else                                                                                                           \
+            hipLaunchKernelGGL((k_gemm_pipe<BDT, EPI_BIAS_F32, WM, TERMS, TM>), grid, block, lds, st, Ahi, Alo, W, T, N, K, bias, outf, ohi, olo, R); \
+    } while (0)
+    if constexpr (WM == 1) {
+        if (T <= 32) PIPE_GO(1);  // the upper half of the 64-row tile alone
+        else PIPE_GO(2);
+    } else {
+        PIPE_GO(2);
+    }
+#undef PIPE_GO
     if (R.k_splits > 1 && !defer_sum) {
         const dim3 fgrid(R.n_tiles, R.bm / FIN_ROWS);
         if (epi == EPI_SWIGLU)

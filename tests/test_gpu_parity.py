@@ -782,6 +782,39 @@ def test_prefill_gemms_with_full_rounds_and_a_split_last_round():
         P.gm.set_gemm_plan_cus(0)
 
 
+def test_short_prompts_around_the_half_tile_limit_and_ragged_weight_tiles():
+    """Blocks of at most 32 rows run the 64-row GEMM kernel on the upper half of its tile only (half of the A tile
+    is neither loaded nor read), 33 .. 64 rows on the whole tile; the weights reach both as stored 256-row tiles.
+    The 0.5B-shaped widths leave the last stored tile of most matrices partly empty (896 = 3.5 tiles, 1152 = 4.5,
+    a vocabulary of 1000 = 3.9); the 7B-shaped widths give every GEMM k-slices.  Both sides of the 32-row limit,
+    in both activation modes."""
+    small = synth.QWEN_0P5B.with_(name="0.5b-l2-v1000", vocab=1000, max_seq_len=160)
+    Q = Pair(small, n_layers=2)
+    try:
+        for T in (31, 32, 33, 64):
+            Q.om.kv_reset(0); Q.gm.kv_reset(0)
+            Q.prefill(synth.make_prompt(small, T, seed=100 + T), where=f"0.5b-width, T={T}")
+            Q.check_kv([0, 1], [0, T - 1, T])
+        tok = Q.decode(5, "decode after a 64-row prompt")
+        _check_verify(Q, np.array([tok, 7, 9, 11, 13, 15, 17], dtype=np.int32), "0.5b-width verify m=7")
+    finally:
+        Q.close()
+    shape = synth.QWEN_7B.with_(name="7b-l2", vocab=4096, max_seq_len=8192 + 8)
+    P = _get_7b_l2(shape)
+    try:
+        for T in (32, 33):
+            P.om.kv_reset(0); P.gm.kv_reset(0)
+            P.prefill(synth.make_prompt(shape, T, seed=200 + T), where=f"7b-width, T={T}")
+        P.gm.set_prefill_precision(binding.EDGEFM_PREFILL_F16)
+        for T in (32, 33):
+            P.om.kv_reset(0); P.gm.kv_reset(0)
+            o = P.om.prefill(synth.make_prompt(shape, T, seed=300 + T))
+            g_next, g_logits = P.gm.prefill(synth.make_prompt(shape, T, seed=300 + T))
+            assert rel_l2(g_logits, o["logits"]) <= F16_MODE_TOL, (T, rel_l2(g_logits, o["logits"]))
+    finally:
+        P.gm.set_prefill_precision(binding.EDGEFM_PREFILL_F16X2)
+
+
 def test_long_prefill_7b_width_two_layers():
     """Prefill GEMMs and flash attention at T = 2048 on the 7B-shaped width (depth 2), then the VLM-shaped
     request: 1024 embedding rows + 64 tokens in one prefill and an 8-token greedy decode (configs[4])."""
