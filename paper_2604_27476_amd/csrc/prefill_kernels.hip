@@ -308,8 +308,9 @@ k_gemm(const uint16_t *__restrict__ Ahi, const uint16_t *__restrict__ Alo, const
 // eight waves in 4 x 2, each wave 64 x 128 (WM = 4: TM = 2, TN = 4, 0.5 LDS fragment reads per MFMA); or, for
 // prompts that would leave most of a 256-row tile empty, 128 x 256 x 32 with the waves in 2 x 4, each 64 x 64
 // (WM = 2); or, for blocks of at most 64 rows (verify steps, very short prompts), 64 x 256 x 32 with the waves
-// in 1 x 8, each 64 x 32 (WM = 1: little MFMA work per k-tile, the loop runs at the pace of its barriers and
-// streams the weights).  The three
+// in 1 x 8, each 64 x 32 (WM = 1: little MFMA work per k-tile, the loop streams the weights at the pace of its
+// LDS reads -- every wave reads the whole A tile -- so blocks of at most 32 rows use the upper half of the
+// tile only, TM = 1, and two workgroups share a CU).  The three
 // operand tiles go from global memory straight into LDS (global_load_lds, no staging registers, no
 // ds_write) through a ring of three stages, two to three k-tiles ahead of the MFMAs, with one barrier per
 // k-tile.  LDS rows are 64 bytes (4 chunks of 16 B); chunk c of row r sits in slot c ^ ((r >> 1) & 3),
