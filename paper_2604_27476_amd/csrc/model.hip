@@ -644,7 +644,11 @@ int edgefm_verify_step(edgefm_model *m, const int32_t *tok_host, uint32_t n_toke
     float *vlogits = m->at<float>(m->L.vlogits);
     const int *subset = m->n_subset ? m->at<int>(m->L.subset) : nullptr;
     const float *src = vlogits;
-    m->verify_was_gemv = m->multi_ok && multi_supported(D, m->G, T);
+    // Four positions at a large shape run faster as a GEMM (7B-shaped: 3.9 against 4.2 ms); at small shapes the
+    // GEMV route's fewer launches win (0.5B-shaped: 1.37 against 1.60 ms, 1.5B-shaped: 2.09 against 2.15).
+    const size_t layer_bytes = 2 * ((size_t)D.R() * D.H + (size_t)D.H * D.qd() + 3 * (size_t)D.I * D.H);
+    const bool gemm_faster = T == MULTI_MAX && layer_bytes >= ((size_t)200 << 20);
+    m->verify_was_gemv = m->multi_ok && multi_supported(D, m->G, T) && !gemm_faster;
     if (m->verify_was_gemv) {
         // Short blocks: the decode kernels with M activation vectors -- one pass over the weights, GEMV streaming
         // rate, attention per position over the cache (which the QKV epilogue has just extended by the block).
