@@ -306,7 +306,7 @@ __global__ void __launch_bounds__(256)
 k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, const uint16_t *__restrict__ vc,
               const int *__restrict__ d_pos, float *__restrict__ part, uint32_t *__restrict__ counters,
               float *__restrict__ o, uint16_t *__restrict__ ohi, uint16_t *__restrict__ olo, int max_seq, int S,
-              float scale, WarmJob warm) {
+              int chunk_min, float scale, WarmJob warm) {
     constexpr int LPR = D / 8;       // lanes per row
     constexpr int RW = WAVE / LPR;   // rows per wave per load
     constexpr int UR = 4;            // loads in flight per lane (K and V each)
@@ -328,7 +328,7 @@ k_attn_decode(const float *__restrict__ q, const uint16_t *__restrict__ kc, cons
     part += (size_t)zq * gridDim.y * GQ * S * (D + 4);
     counters += zq * gridDim.y;
     int chunk = (n_keys + S - 1) / S;
-    if (chunk < ATTN_CHUNK_MIN) chunk = ATTN_CHUNK_MIN;
+    if (chunk < chunk_min) chunk = chunk_min;
     const int n_active = (n_keys + chunk - 1) / chunk;
     if (s >= n_active) {
         // No slice of the context for this workgroup.  The attention is bound by latency and leaves HBM idle, so
@@ -709,13 +709,13 @@ void launch_fill_u16(uint16_t *p, size_t n, uint16_t v, hipStream_t st) {
 template <int KDT, int DD>
 static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
                           const int *d_pos, float *part, uint32_t *counters, float *o, uint16_t *ohi, uint16_t *olo,
-                          const WarmJob &warm, int n_queries, int n_slices, hipStream_t st) {
+                          const WarmJob &warm, int n_queries, int n_slices, int chunk_min, hipStream_t st) {
     const dim3 grid(n_slices, D.nkv, n_queries), block(256);
     const float scale = 1.0f / sqrtf((float)D.d);
 #define ATTN_CASE(GQ)                                                                                          \
     case GQ:                                                                                                   \
         hipLaunchKernelGGL((k_attn_decode<KDT, DD, GQ>), grid, block, 0, st, q, kc, vc, d_pos, part, counters, o, \
-                           ohi, olo, D.max_seq, G.attn_splits, scale, warm);                                   \
+                           ohi, olo, D.max_seq, G.attn_splits, chunk_min, scale, warm);                        \
         break;
     switch (D.g()) {
         ATTN_CASE(1) ATTN_CASE(2) ATTN_CASE(3) ATTN_CASE(4) ATTN_CASE(5) ATTN_CASE(6) ATTN_CASE(7) ATTN_CASE(8)
@@ -730,13 +730,21 @@ void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint1
     // Context slices to launch.  A captured step cannot know the context length, so it launches all of them and
     // the ones beyond the context return at once (or warm W_o); a caller that knows the length (host_ctx > 0:
     // keys 0 .. host_ctx - 1 for the last query) launches only the slices some query uses, by the kernel's own rule.
-    int n_slices = G.attn_splits;
+    int n_slices = G.attn_splits, chunk_min = ATTN_CHUNK_MIN;
     if (host_ctx > 0) {
+        // Several queries: the kernel's register count lets two workgroups share a CU, and a launch with more
+        // workgroups than that runs in rounds (8 queries x 4 KV heads x 17 slices of 64 keys: a second round for 32
+        // of 544 workgroups, 24.6 us against 13.7 for one query).  Longer slices instead, whole loop passes of 64 keys.
+        if (n_queries > 1) {
+            const int max_slices = std::max(1, 2 * G.n_cu / (D.nkv * n_queries));
+            const int need = (host_ctx + max_slices - 1) / max_slices;
+            chunk_min = std::max(ATTN_CHUNK_MIN, (need + 63) / 64 * 64);
+        }
         n_slices = 1;
         for (int z = 0; z < n_queries; ++z) {
             const int n_keys = host_ctx - (n_queries - 1 - z);
             int chunk = (n_keys + G.attn_splits - 1) / G.attn_splits;
-            if (chunk < ATTN_CHUNK_MIN) chunk = ATTN_CHUNK_MIN;
+            if (chunk < chunk_min) chunk = chunk_min;
             n_slices = std::max(n_slices, (n_keys + chunk - 1) / chunk);
         }
     }
@@ -751,14 +759,14 @@ void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint1
         warm.n_wg = g.blocks;
     }
     if (D.kvdt == DT_BF16) {
-        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
-        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+        if (D.d == 128) attn_launch_g<DT_BF16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, chunk_min, st);
+        else attn_launch_g<DT_BF16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, chunk_min, st);
     } else if (D.kvdt == DT_FP8) {
-        if (D.d == 128) attn_launch_g<DT_FP8, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
-        else attn_launch_g<DT_FP8, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+        if (D.d == 128) attn_launch_g<DT_FP8, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, chunk_min, st);
+        else attn_launch_g<DT_FP8, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, chunk_min, st);
     } else {
-        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
-        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, st);
+        if (D.d == 128) attn_launch_g<DT_F16, 128>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, chunk_min, st);
+        else attn_launch_g<DT_F16, 64>(D, G, q, kc, vc, d_pos, part, counters, o, ohi, olo, warm, n_queries, n_slices, chunk_min, st);
     }
 }
 

@@ -42,9 +42,10 @@ struct Layout {
 constexpr int ATTN_SPLITS = 64;
 constexpr int MAX_PARTIALS = 4096;
 constexpr uint32_t VERIFY_MAX = 32;  // positions per verify step (sizes its logits buffers)
-// Blocks up to this length run their attention on the decode kernel, one grid layer per position (measured at
-// context 1024, 7B shape: faster than the flash kernel up to 16 positions, slower at 32).
-constexpr int SHORT_ATTN_MAX = 16;
+// Blocks up to this length run their attention on the decode kernel, one grid layer per position and context
+// slices long enough for the launch to be resident at once (measured at context 1024, 7B shape: faster than the
+// K/V copies + flash kernel + merge for every block length up to 32).
+constexpr int SHORT_ATTN_MAX = 32;
 static_assert(SHORT_ATTN_MAX >= MULTI_MAX, "the multi-position decode kernels share the attention scratch");
 static_assert(VERIFY_MAX * 32 <= MAX_PARTIALS, "row-argmax partials share the lm_head partial buffers");
 

@@ -561,7 +561,8 @@ def test_short_verify_step_replays_equal_the_eager_sequence(monkeypatch):
 
 
 def test_short_block_attention_routes_agree(monkeypatch):
-    """Blocks of at most 16 positions on the GEMM route take the decode attention (one grid layer per position);
+    """Blocks of at most 32 positions on the GEMM route take the decode attention (one grid layer per position,
+    context slices sized so that the whole launch is resident at once);
     EDGEFM_SHORT_ATTN=flash at load time keeps them on the flash-attention kernel.  Both against the oracle and
     against each other, for verify blocks over a context and for a short prompt from an empty context."""
     shape = TINY_BF16.with_(max_seq_len=200)
@@ -573,7 +574,7 @@ def test_short_block_attention_routes_agree(monkeypatch):
     prompt = synth.make_prompt(shape, 70)
     P.prefill(prompt)
     flash.prefill(prompt, want_logits=False)
-    for m in (5, 8, 16, 17, 13):
+    for m in (5, 8, 16, 17, 32, 13):
         block = rng.integers(0, shape.vocab, size=m).astype(np.int32)
         o = P.om.forward(block, logits="all")
         na, la = P.gm.verify_step(block, want_logits=True)
@@ -583,8 +584,8 @@ def test_short_block_attention_routes_agree(monkeypatch):
             assert rel_l2(la[i], lb[i]) <= 2e-4
             check_token(int(na[i]), o["logits"][i], f"decode-attention route m={m} row {i}")
             check_token(int(nb[i]), o["logits"][i], f"flash route m={m} row {i}")
-    P.check_kv([0, 1], [69, 70, 74, 128])
-    for T in (1, 16, 17):                                # short prompts from an empty context
+    P.check_kv([0, 1], [69, 70, 74, 160, 161])
+    for T in (1, 16, 17, 32, 33):                        # short prompts from an empty context
         P.om.kv_reset(0); P.gm.kv_reset(0); flash.kv_reset(0)
         pr = synth.make_prompt(shape, T, seed=77 + T)
         P.prefill(pr, where=f"short prompt T={T}")
@@ -644,9 +645,9 @@ def test_verify_step_7b_width_context_1000():
         P.gm.kv_write(l, k, v)
     P.gm.set_kv_len(ctx)
     rng = np.random.default_rng(4)
-    for m in (4, 8, 3, 2):
+    for m in (4, 8, 3, 2, 16):
         _check_verify(P, rng.integers(0, shape.vocab, size=m).astype(np.int32), f"7b-width verify m={m}")
-    assert P.gm.kv_len == ctx + 17
+    assert P.gm.kv_len == ctx + 33
     print(f"verify 7b-width worst {P.worst}")
 
 
