@@ -211,6 +211,16 @@ int edgefm_debug_launch_op(edgefm_model *m, int op, int layer, uint32_t repeat);
  * Errors: INVALID_ARG (NULL, a zero size, n_cu not in 1..256). */
 int edgefm_debug_gemm_plan(uint32_t T, uint32_t N, uint32_t K, int swiglu, uint32_t n_cu, int32_t *out_host);
 
+/* Test-only, host arithmetic (no device call): how the attention of a block of n_positions new positions
+ * (Section 3.10 decode attention, one grid layer per position of a verify block or short prompt, Section 3.11) is
+ * cut along a context of `context` keys (the keys the last position sees, the block included) on n_cu compute
+ * units (1..256) with n_kv_heads KV heads.  out_host[0] = minimum slice length in keys (a multiple of 64),
+ * out_host[1] = context slices launched per (KV head, position); every slice is served by one workgroup and the
+ * slices of a (KV head, position) are merged in slice order.  out_host: host memory, 2 int32, caller-owned.
+ * Returns EDGEFM_ERR_INVALID_ARG for a null pointer, counts of zero, n_cu > 256, more than 32 positions or a
+ * context shorter than the block. */
+int edgefm_debug_attn_slices(uint32_t n_cu, uint32_t n_kv_heads, uint32_t n_positions, uint32_t context, int32_t *out_host);
+
 /* Test-only, process-wide: plan the cuts of the prefill GEMMs as for n_cu compute units (1..256) instead of the
  * device's count; 0 restores.  A small n_cu makes short prompts take the cuts that otherwise need thousands of
  * rows (full rounds of tiles followed by a k-sliced last round).  Results do not depend on it beyond summation

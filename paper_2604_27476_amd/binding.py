@@ -28,7 +28,7 @@ EXPORTS = [
     "edgefm_kv_len", "edgefm_model_free", "edgefm_strerror", "edgefm_last_hip_error", "edgefm_debug_kv_read",
     "edgefm_debug_kv_write", "edgefm_debug_kv_fill", "edgefm_debug_set_kv_len", "edgefm_debug_last_hidden",
     "edgefm_debug_launch_op", "edgefm_debug_stage_trace", "edgefm_set_vocab_subset", "edgefm_verify_step",
-    "edgefm_debug_verify_hidden", "edgefm_set_prefill_precision", "edgefm_debug_gemm_plan",
+    "edgefm_debug_verify_hidden", "edgefm_set_prefill_precision", "edgefm_debug_gemm_plan", "edgefm_debug_attn_slices",
     "edgefm_debug_set_gemm_plan_cus",
 ]
 
@@ -70,6 +70,7 @@ def load_library():
     lib.edgefm_kv_len.argtypes = [m]
     lib.edgefm_set_prefill_precision.argtypes = [m, C.c_int]
     lib.edgefm_debug_gemm_plan.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, C.c_uint32, C.c_void_p]
+    lib.edgefm_debug_attn_slices.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
     lib.edgefm_debug_set_gemm_plan_cus.argtypes = [C.c_uint32]
     lib.edgefm_kv_len.restype = C.c_uint32
     lib.edgefm_model_free.argtypes = [m]

@@ -724,6 +724,31 @@ static void attn_launch_g(const Dims &D, const Geo &G, const float *q, const uin
 #undef ATTN_CASE
 }
 
+// Slices of a launch whose context length the host knows (keys 0 .. host_ctx - 1 for the last of n_queries
+// positions, one key fewer for each earlier one): the minimum slice length the kernel is to use and the number of
+// slices to launch (host arithmetic only).  One position: slices of at least 64 keys, at most max_splits of them.
+// Several positions: the kernel's register count lets two workgroups share a CU, and a launch with more
+// workgroups than that runs in rounds (8 positions x 4 KV heads x 17 slices of 64 keys: a second round for 32 of
+// 544 workgroups, 24.6 us against 13.7 for one position), so the slices get longer instead, by whole loop passes
+// of 64 keys, until slices x KV heads x positions fits.
+void attn_slice_plan(int n_cu, int n_kv, int n_queries, int host_ctx, int max_splits, int *chunk_min, int *n_slices) {
+    int cmin = ATTN_CHUNK_MIN;
+    if (n_queries > 1) {
+        const int max_slices = std::max(1, 2 * n_cu / (n_kv * n_queries));
+        const int need = (host_ctx + max_slices - 1) / max_slices;
+        cmin = std::max(ATTN_CHUNK_MIN, (need + 63) / 64 * 64);
+    }
+    int ns = 1;
+    for (int z = 0; z < n_queries; ++z) {
+        const int n_keys = host_ctx - (n_queries - 1 - z);
+        int chunk = (n_keys + max_splits - 1) / max_splits;
+        if (chunk < cmin) chunk = cmin;
+        ns = std::max(ns, (n_keys + chunk - 1) / chunk);
+    }
+    *chunk_min = cmin;
+    *n_slices = ns;
+}
+
 void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint16_t *kc, const uint16_t *vc,
                         const int *d_pos, float *part, uint32_t *counters, float *o, uint16_t *ohi, uint16_t *olo,
                         const uint16_t *warm_w, int n_queries, int host_ctx, hipStream_t st) {
@@ -731,23 +756,7 @@ void launch_attn_decode(const Dims &D, const Geo &G, const float *q, const uint1
     // the ones beyond the context return at once (or warm W_o); a caller that knows the length (host_ctx > 0:
     // keys 0 .. host_ctx - 1 for the last query) launches only the slices some query uses, by the kernel's own rule.
     int n_slices = G.attn_splits, chunk_min = ATTN_CHUNK_MIN;
-    if (host_ctx > 0) {
-        // Several queries: the kernel's register count lets two workgroups share a CU, and a launch with more
-        // workgroups than that runs in rounds (8 queries x 4 KV heads x 17 slices of 64 keys: a second round for 32
-        // of 544 workgroups, 24.6 us against 13.7 for one query).  Longer slices instead, whole loop passes of 64 keys.
-        if (n_queries > 1) {
-            const int max_slices = std::max(1, 2 * G.n_cu / (D.nkv * n_queries));
-            const int need = (host_ctx + max_slices - 1) / max_slices;
-            chunk_min = std::max(ATTN_CHUNK_MIN, (need + 63) / 64 * 64);
-        }
-        n_slices = 1;
-        for (int z = 0; z < n_queries; ++z) {
-            const int n_keys = host_ctx - (n_queries - 1 - z);
-            int chunk = (n_keys + G.attn_splits - 1) / G.attn_splits;
-            if (chunk < chunk_min) chunk = chunk_min;
-            n_slices = std::max(n_slices, (n_keys + chunk - 1) / chunk);
-        }
-    }
+    if (host_ctx > 0) attn_slice_plan(G.n_cu, D.nkv, n_queries, host_ctx, G.attn_splits, &chunk_min, &n_slices);
     WarmJob warm = {nullptr, 0, 0, 0};
     static const bool warm_on = !(getenv("EDGEFM_WARM") && getenv("EDGEFM_WARM")[0] == '0');
     // worthwhile only where the matrix fits the L2s (4 MB per XCD) with room to spare, and the slices map to XCDs

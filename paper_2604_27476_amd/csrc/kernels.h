@@ -164,6 +164,8 @@ struct PipeRange {
 void launch_gemm(const Dims &D, int epi, const uint16_t *Ahi, const uint16_t *Alo, const uint16_t *W16, int T, int N,
                  int K, const uint16_t *bias, float *out_f32, uint16_t *out_hi, uint16_t *out_lo, float *ws,
                  PipeRange *pending, hipStream_t st);
+// Context slices of a decode-attention launch over a context the host knows (see decode_kernels.hip); host arithmetic
+void attn_slice_plan(int n_cu, int n_kv, int n_queries, int host_ctx, int max_splits, int *chunk_min, int *n_slices);
 // The cut of a GEMM as launch_gemm would make it on n_cu compute units (host arithmetic, no device call):
 // out = {tile rows, row tiles, column tiles, tiles, tiles in full rounds, tiles of the last round, k-slices of
 // those, 1 if the pipelined kernel takes the GEMM}

@@ -760,6 +760,17 @@ int edgefm_debug_gemm_plan(uint32_t T, uint32_t N, uint32_t K, int swiglu, uint3
     return EDGEFM_OK;
 }
 
+int edgefm_debug_attn_slices(uint32_t n_cu, uint32_t n_kv_heads, uint32_t n_positions, uint32_t context, int32_t *out_host) {
+    if (!out_host || n_cu < 1 || n_cu > 256 || n_kv_heads < 1 || n_kv_heads > 1024 || n_positions < 1 ||
+        n_positions > VERIFY_MAX || context < n_positions || context > (1u << 20))
+        return EDGEFM_ERR_INVALID_ARG;
+    int chunk_min = 0, n_slices = 0;
+    attn_slice_plan((int)n_cu, (int)n_kv_heads, (int)n_positions, (int)context, ATTN_SPLITS, &chunk_min, &n_slices);
+    out_host[0] = chunk_min;
+    out_host[1] = n_slices;
+    return EDGEFM_OK;
+}
+
 int edgefm_debug_set_gemm_plan_cus(uint32_t n_cu) {
     if (n_cu > 256) return EDGEFM_ERR_INVALID_ARG;
     debug_set_gemm_plan_cus((int)n_cu);

@@ -182,3 +182,42 @@ def test_workload_shapes_and_decode_byte_counts_match_the_fixture():
         assert step == step_bytes == s.weight_bytes_per_token()
         assert L * 2 * nkv * d * 2 == kv_bytes == s.kv_bytes_per_context_token()
     assert synth.SHAPES["qwen2.5-7b-shaped"].weight_bytes_per_token() / 1e9 == pytest.approx(14.141, abs=1e-3)
+
+
+def _attn(lib, n_cu, n_kv, m, ctx):
+    out = np.zeros(2, np.int32)
+    assert lib.edgefm_debug_attn_slices(n_cu, n_kv, m, ctx, out.ctypes.data_as(C.c_void_p)) == binding.EDGEFM_OK
+    return int(out[0]), int(out[1])
+
+
+def test_attention_slices_known_cuts_and_invariants(lib):
+    """Host logic of the decode attention over a context the host knows: one position is cut into slices of at
+    least 64 keys, at most 64 slices; a block of positions gets slices long enough for slices x KV heads x
+    positions to fit two workgroups per compute unit."""
+    assert _attn(lib, 256, 4, 1, 1024) == (64, 16)
+    assert _attn(lib, 256, 4, 1, 1025) == (64, 17)
+    assert _attn(lib, 256, 4, 1, 8192) == (64, 64)          # 128 keys per slice: the slice count is capped, not the length
+    assert _attn(lib, 256, 4, 5, 1029) == (64, 17)          # 5 x 4 x 17 = 340 workgroups: fits
+    assert _attn(lib, 256, 4, 8, 1032) == (128, 9)          # 17 slices would be 544 workgroups
+    assert _attn(lib, 256, 4, 16, 1040) == (192, 6)
+    assert _attn(lib, 256, 4, 32, 1056) == (320, 4)
+    for n_cu in (256, 64, 8):
+        for n_kv in (1, 2, 4, 8):
+            for m in (1, 2, 4, 7, 16, 32):
+                for ctx in (m, 63 + m, 64 + m, 1000, 4096, 8192 + m, 100000):
+                    cmin, ns = _attn(lib, n_cu, n_kv, m, ctx)
+                    assert cmin % 64 == 0 and cmin >= 64 and 1 <= ns <= 64
+                    chunk = max(-(-ctx // 64), cmin)            # slice length of the last position
+                    assert ns == -(-ctx // chunk)               # the longest context of the block sets the launch
+                    if m > 1 and chunk == cmin:                 # sized by the residency rule, unless one slice per ...
+                        assert ns * n_kv * m <= 2 * n_cu or ns == 1
+                    if m == 1:
+                        assert cmin == 64
+
+
+def test_attention_slices_rejects_bad_arguments(lib):
+    out = np.zeros(2, np.int32)
+    ptr = out.ctypes.data_as(C.c_void_p)
+    for args in ((0, 4, 1, 100), (257, 4, 1, 100), (256, 0, 1, 100), (256, 4, 0, 100), (256, 4, 33, 100), (256, 4, 8, 7)):
+        assert lib.edgefm_debug_attn_slices(*args, ptr) == binding.EDGEFM_ERR_INVALID_ARG
+    assert lib.edgefm_debug_attn_slices(256, 4, 1, 100, None) == binding.EDGEFM_ERR_INVALID_ARG
