@@ -23,7 +23,7 @@ __global__ void k_embed_m(const uint16_t *__restrict__ E, const int *__restrict_
 // fused QKV for M positions: RMSNorm prologue per position, GEMV, bias + RoPE at pos + m + cache write epilogue.
 // Work unit = the rotation partners (i, i + d/2) of one head, as in k_qkv.  q is [M][n_q d].
 template <int DT, int KDT, int M>
-__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
 k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const uint16_t *__restrict__ gain,
         const float *__restrict__ x, const float *__restrict__ rope_cos, const float *__restrict__ rope_sin,
         const int *__restrict__ d_pos, float *__restrict__ q, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
@@ -97,7 +97,7 @@ k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const
 // (down projection: M x 76 KB) they are staged in slices of slice_vec 16-byte words along K, and the wave keeps
 // its partial dot products in registers from slice to slice.
 template <int DT, int M>
-__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
 k_gemv_resid_m(const uint16_t *__restrict__ W, const float *__restrict__ vec, float *__restrict__ x, int rows_n, int K,
                int slice_vec) {
     extern __shared__ float4 smem[];
@@ -133,7 +133,7 @@ k_gemv_resid_m(const uint16_t *__restrict__ W, const float *__restrict__ vec, fl
 
 // h[m][j] = silu(W_gate[j] . RMSNorm(x[m])) * (W_up[j] . RMSNorm(x[m])); unit j = rows (j, I + j)
 template <int DT, int M>
-__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
 k_gateup_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
            float *__restrict__ h, int H, int I, float eps) {
     extern __shared__ float4 smem[];
@@ -174,7 +174,7 @@ k_gateup_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, co
 // logits[m][i] = W_lm[token(i)] . RMSNorm(x[m]) for the n_rows candidate rows (the whole vocabulary, or the
 // ascending ids of `subset`); hidden[m] = RMSNorm(x[m]).  The greedy choice is left to launch_argmax_rows.
 template <int DT, int M>
-__global__ void __launch_bounds__(512)  // 8 waves: a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
 k_lmhead_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
            float *__restrict__ logits, float *__restrict__ hidden, int H, int n_rows, float eps,
            const int *__restrict__ subset) {
@@ -234,10 +234,12 @@ namespace {
 struct Grid {
     int blocks, threads;
 };
-// about one workgroup per CU, each wave owning whole units (same policy as the single-position kernels)
-Grid multi_grid(int n_units, int n_cu) {
+// about one workgroup per CU, each wave owning whole units (same policy as the single-position kernels); sixteen
+// waves where the kernels fit 128 registers (M <= 2: 2 % faster than eight), eight otherwise
+Grid multi_grid(int n_units, int n_cu, int M) {
     const int per_cu = (n_units + n_cu - 1) / n_cu;
-    const int waves = per_cu < 4 ? 4 : (per_cu > 8 ? 8 : per_cu);
+    const int max_waves = M <= 2 ? 16 : 8;
+    const int waves = per_cu < 4 ? 4 : (per_cu > max_waves ? max_waves : per_cu);
     int blocks = (n_units + waves - 1) / waves;
     if (blocks > n_cu) blocks = n_cu;
     return {blocks, waves * 64};
@@ -283,7 +285,7 @@ bool multi_supported(const Dims &D, const Geo &G, int M) {
     // the staged vectors of the QKV / gate-up / lm_head prologues have to fit LDS together ...
     if ((size_t)M * D.H * 4 > MULTI_LDS_BYTES || (size_t)M * D.qd() * 4 > MULTI_LDS_BYTES) return false;
     // ... and the residual GEMVs keep one pair of rows per wave
-    const Grid g = multi_grid((D.H + 1) / 2, G.n_cu);
+    const Grid g = multi_grid((D.H + 1) / 2, G.n_cu, M);
     return (size_t)g.blocks * (g.threads / 64) >= (size_t)(D.H + 1) / 2;
 }
 
@@ -294,7 +296,7 @@ void launch_embed_m(const Dims &D, int M, const uint16_t *embed, const int *d_to
 void launch_qkv_m(const Dims &D, const Geo &G, int M, const LayerW &W, const float *x, const float *rope_cos,
                   const float *rope_sin, const int *d_pos, float *q, uint16_t *kc, uint16_t *vc, hipStream_t st) {
     const size_t lds = (size_t)M * D.H * 4;
-    const Grid g = multi_grid((D.nq + 2 * D.nkv) * (D.d / 2), G.n_cu);
+    const Grid g = multi_grid((D.nq + 2 * D.nkv) * (D.d / 2), G.n_cu, M);
     const uint16_t *bias = D.qkv_bias ? W.bqkv : nullptr;
 #define QKV_CALL(KDT)                                                                                                  \
     M_SWITCH(M, hipLaunchKernelGGL((k_qkv_m<DT, KDT, M>), dim3(g.blocks), dim3(g.threads), lds, st, W.wqkv, bias,      \
@@ -311,14 +313,14 @@ void launch_gemv_resid_m(const Dims &D, const Geo &G, int M, const uint16_t *W, 
     slice_vec -= slice_vec % (64 * 7);                          // whole passes of a wave
     if (slice_vec > nvec) slice_vec = nvec;
     const size_t lds = (size_t)M * slice_vec * 32;
-    const Grid g = multi_grid((D.H + 1) / 2, G.n_cu);
+    const Grid g = multi_grid((D.H + 1) / 2, G.n_cu, M);
     DT_SWITCH(D.wdt, M_SWITCH(M, hipLaunchKernelGGL((k_gemv_resid_m<DT, M>), dim3(g.blocks), dim3(g.threads), lds, st, W,
                                                     vec, x, D.H, K, slice_vec);))
 }
 
 void launch_gateup_m(const Dims &D, const Geo &G, int M, const LayerW &W, const float *x, float *h, hipStream_t st) {
     const size_t lds = (size_t)M * D.H * 4;
-    const Grid g = multi_grid(D.I, G.n_cu);
+    const Grid g = multi_grid(D.I, G.n_cu, M);
     DT_SWITCH(D.wdt, M_SWITCH(M, hipLaunchKernelGGL((k_gateup_m<DT, M>), dim3(g.blocks), dim3(g.threads), lds, st,
                                                     W.w_gate_up, W.mlp_norm, x, h, D.H, D.I, D.eps);))
 }
@@ -327,7 +329,7 @@ void launch_lmhead_m(const Dims &D, const Geo &G, int M, const uint16_t *lm, con
                      float *logits, float *hidden, const int *subset, int n_subset, hipStream_t st) {
     const size_t lds = (size_t)M * D.H * 4;
     const int n_rows = subset ? n_subset : D.V;
-    const Grid g = multi_grid((n_rows + 1) / 2, G.n_cu);
+    const Grid g = multi_grid((n_rows + 1) / 2, G.n_cu, M);
     DT_SWITCH(D.wdt, M_SWITCH(M, hipLaunchKernelGGL((k_lmhead_m<DT, M>), dim3(g.blocks), dim3(g.threads), lds, st, lm,
                                                     final_norm, x, logits, hidden, D.H, n_rows, D.eps, subset);))
 }
