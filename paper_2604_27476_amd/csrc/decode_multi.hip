@@ -23,7 +23,7 @@ __global__ void k_embed_m(const uint16_t *__restrict__ E, const int *__restrict_
 // fused QKV for M positions: RMSNorm prologue per position, GEMV, bias + RoPE at pos + m + cache write epilogue.
 // Work unit = the rotation partners (i, i + d/2) of one head, as in k_qkv.  q is [M][n_q d].
 template <int DT, int KDT, int M>
-__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : (M == 3 ? 768 : 512))  // up to 16 waves; M = 3: 12, M = 4: 8 (170 and 256 registers: M accumulator sets + the chunk)
 k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const uint16_t *__restrict__ gain,
         const float *__restrict__ x, const float *__restrict__ rope_cos, const float *__restrict__ rope_sin,
         const int *__restrict__ d_pos, float *__restrict__ q, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc,
@@ -97,7 +97,7 @@ k_qkv_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ bias, const
 // (down projection: M x 76 KB) they are staged in slices of slice_vec 16-byte words along K, and the wave keeps
 // its partial dot products in registers from slice to slice.
 template <int DT, int M>
-__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : (M == 3 ? 768 : 512))  // up to 16 waves; M = 3: 12, M = 4: 8 (170 and 256 registers: M accumulator sets + the chunk)
 k_gemv_resid_m(const uint16_t *__restrict__ W, const float *__restrict__ vec, float *__restrict__ x, int rows_n, int K,
                int slice_vec) {
     extern __shared__ float4 smem[];
@@ -133,7 +133,7 @@ k_gemv_resid_m(const uint16_t *__restrict__ W, const float *__restrict__ vec, fl
 
 // h[m][j] = silu(W_gate[j] . RMSNorm(x[m])) * (W_up[j] . RMSNorm(x[m])); unit j = rows (j, I + j)
 template <int DT, int M>
-__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : (M == 3 ? 768 : 512))  // up to 16 waves; M = 3: 12, M = 4: 8 (170 and 256 registers: M accumulator sets + the chunk)
 k_gateup_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
            float *__restrict__ h, int H, int I, float eps) {
     extern __shared__ float4 smem[];
@@ -174,7 +174,7 @@ k_gateup_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, co
 // logits[m][i] = W_lm[token(i)] . RMSNorm(x[m]) for the n_rows candidate rows (the whole vocabulary, or the
 // ascending ids of `subset`); hidden[m] = RMSNorm(x[m]).  The greedy choice is left to launch_argmax_rows.
 template <int DT, int M>
-__global__ void __launch_bounds__(M <= 2 ? 1024 : 512)  // up to 16 waves; M > 2: 8, a 256-register budget (M accumulator sets + the chunk)
+__global__ void __launch_bounds__(M <= 2 ? 1024 : (M == 3 ? 768 : 512))  // up to 16 waves; M = 3: 12, M = 4: 8 (170 and 256 registers: M accumulator sets + the chunk)
 k_lmhead_m(const uint16_t *__restrict__ W, const uint16_t *__restrict__ gain, const float *__restrict__ x,
            float *__restrict__ logits, float *__restrict__ hidden, int H, int n_rows, float eps,
            const int *__restrict__ subset) {
@@ -234,11 +234,12 @@ namespace {
 struct Grid {
     int blocks, threads;
 };
-// about one workgroup per CU, each wave owning whole units (same policy as the single-position kernels); sixteen
-// waves where the kernels fit 128 registers (M <= 2: 2 % faster than eight), eight otherwise
+// about one workgroup per CU, each wave owning whole units (same policy as the single-position kernels); as many
+// waves as the kernels' registers allow: sixteen for M <= 2 (2 % faster than eight), twelve for M = 3 (3 %), eight for M = 4
+// (twelve measured the same there)
 Grid multi_grid(int n_units, int n_cu, int M) {
     const int per_cu = (n_units + n_cu - 1) / n_cu;
-    const int max_waves = M <= 2 ? 16 : 8;
+    const int max_waves = M <= 2 ? 16 : (M == 3 ? 12 : 8);
     const int waves = per_cu < 4 ? 4 : (per_cu > max_waves ? max_waves : per_cu);
     int blocks = (n_units + waves - 1) / waves;
     if (blocks > n_cu) blocks = n_cu;
